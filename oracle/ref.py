@@ -1,0 +1,117 @@
+"""ctypes front end of the fp64 CPU oracle (TEST INFRASTRUCTURE ONLY).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import
+this module; the product path never does.  It compiles
+``rl_decode_attn_ref.c`` with gcc on demand and calls it on numpy arrays.
+bf16 tensors are passed as ``uint16`` bit patterns.
+
+The definition the C code follows (paper Sec. 2.2, Sec. 3.1 "The MDP of
+RLLaVA", Algorithm 1, Sec. 3.2.2 "Sampling stage") is stated in
+``rl_decode_attn_ref.h``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rl_decode_attn_ref.c")
+_HDR = os.path.join(_HERE, "rl_decode_attn_ref.h")
+_LIB = os.path.join(_HERE, "librl_decode_attn_ref.so")
+
+F32, BF16 = 0, 1
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle shared object with gcc (plain C, OpenMP)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_HDR)))
+    if force or stale:
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        lib.rl_decode_attn_ref_f64.restype = ip
+        lib.rl_decode_attn_ref_f64.argtypes = [ip] * 8 + [ctypes.c_double] + [vp] * 9 + [
+            vp, ctypes.c_int64, ip, ctypes.POINTER(ip)]
+        lib.rl_lse_combine_ref_f64.restype = None
+        lib.rl_lse_combine_ref_f64.argtypes = [ip, ip, vp, vp, vp, vp]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _elem(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens,
+                    scale, G, rows=None, n_threads=0, return_threads=False):
+    """out[B,Hq,d], lse[B,Hq] in fp64.  Shapes as in rl_decode_attn_ref.h.
+
+    ``rows``: optional int array [n,2] of (b, h) pairs; then only those entries
+    are computed and the rest of the returned arrays is NaN.
+    """
+    lib = _load()
+    q = np.ascontiguousarray(q)
+    et = _elem(q)
+    B, Hq, d = q.shape
+    P, Hkv, Lp_cap, _ = k_prefix.shape
+    Ls_cap = k_suffix.shape[2]
+    assert B == P * G and k_suffix.shape[0] == B and k_suffix.shape[1] == Hkv
+    arrs = [np.ascontiguousarray(a) for a in (k_prefix, v_prefix, k_suffix, v_suffix)]
+    for a in arrs:
+        assert _elem(a) == et
+    pl = np.ascontiguousarray(prefix_lens, dtype=np.int32)
+    sl = np.ascontiguousarray(suffix_lens, dtype=np.int32)
+    assert pl.shape == (P,) and sl.shape == (B,)
+    fill = np.nan if rows is not None else 0.0
+    out = np.full((B, Hq, d), fill, dtype=np.float64)
+    lse = np.full((B, Hq), fill, dtype=np.float64)
+    r = None
+    n_rows = 0
+    if rows is not None:
+        r = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 2)
+        n_rows = r.shape[0]
+    used = ctypes.c_int(0)
+    rc = lib.rl_decode_attn_ref_f64(et, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale),
+                                    _ptr(q), _ptr(arrs[0]), _ptr(arrs[1]), _ptr(pl),
+                                    _ptr(arrs[2]), _ptr(arrs[3]), _ptr(sl),
+                                    _ptr(out), _ptr(lse), _ptr(r), n_rows,
+                                    int(n_threads), ctypes.byref(used))
+    if rc != 0:
+        raise ValueError(f"rl_decode_attn_ref_f64 returned {rc}")
+    if return_threads:
+        return out, lse, used.value
+    return out, lse
+
+
+def lse_combine_ref(o_parts, lse_parts):
+    """Merge n partials (o_parts [n,d], lse_parts [n]) -> (out [d], lse)."""
+    lib = _load()
+    o = np.ascontiguousarray(o_parts, dtype=np.float64)
+    l = np.ascontiguousarray(lse_parts, dtype=np.float64)
+    n, d = o.shape
+    out = np.zeros(d, dtype=np.float64)
+    res = np.zeros(1, dtype=np.float64)
+    lib.rl_lse_combine_ref_f64(n, d, _ptr(o), _ptr(l), _ptr(out), _ptr(res))
+    return out, float(res[0])

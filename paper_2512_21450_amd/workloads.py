@@ -1,0 +1,161 @@
+"""Seeded synthetic rollout workloads (input generation only).
+
+This module draws lengths and tensor values; it holds none of the attention
+arithmetic.  Both the GPU path's tests/benchmark and the CPU oracle's tests
+take their inputs from here, as numpy arrays (bf16 tensors are ``uint16`` bit
+patterns, rounded to nearest-even from fp32 draws).
+
+The shapes stand in for the rollouts the paper runs (Sec. 5.1: GRPO with 4-8
+responses per prompt on 2B-7B Qwen-VL policies; Sec. 3.1: the prompt
+s_0 = (x_0, y_0) is an image part plus a text part, every sampled trajectory of
+a group starts from it).  The paper states no token counts; the ones below are
+typical visual-token and response budgets for those models.
+"""
+from __future__ import annotations
+
+import math
+from concurrent.futures import ThreadPoolExecutor
+from dataclasses import dataclass, replace
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    seed: int
+    dtype: str            # "f32" or "bf16": element type of q, k, v
+    P: int                # prompts
+    G: int                # sampled responses per prompt (the GRPO group)
+    Hq: int
+    Hkv: int
+    d: int
+    Lp_cap: int           # row capacity of the prefix KV buffers
+    Ls_cap: int           # row capacity of the per-sequence suffix KV buffers
+    prefix: tuple         # ("const", L) | ("agentic", n_img, img_tokens, lo, hi)
+    suffix: tuple         # ("uniform", hi) | ("lognormal", median, sigma) | ("const", L)
+    q_gain: float = 1.0   # q ~ q_gain * N(0,1)
+    note: str = ""
+
+    @property
+    def B(self) -> int:
+        return self.P * self.G
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / math.sqrt(self.d)
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+
+# The five configurations the throughput metric and the parity bar are stated on.
+WORKLOADS = {
+    "tiny": Workload("tiny", 1001, "f32", 1, 4, 2, 1, 64, 64, 32,
+                     ("const", 64), ("uniform", 32),
+                     note="1 prompt x G=4, 2/1 heads, d=64, prefix 48 image + 16 text"),
+    "vlm3b": Workload("vlm3b", 1002, "bf16", 8, 8, 16, 2, 128, 452, 512,
+                      ("const", 452), ("uniform", 512),
+                      note="8 prompts x G=8, 16/2 heads, prefix 324 visual + 128 text"),
+    "vlm7b": Workload("vlm7b", 1003, "bf16", 32, 8, 28, 4, 128, 1280, 2048,
+                      ("const", 1280), ("uniform", 2048), q_gain=2.0,
+                      note="32 prompts x G=8, 28/4 heads, prefix 1024 visual + 256 text"),
+    "agentic": Workload("agentic", 1004, "bf16", 16, 8, 28, 4, 128, 1344, 4096,
+                        ("agentic", 3, 256, 64, 192), ("lognormal", 300.0, 1.0),
+                        note="16 prompts x G=8, 28/4 heads, 3 x (256 image + 64..192 text)"),
+    "highbatch": Workload("highbatch", 1005, "bf16", 128, 16, 16, 2, 128, 640, 1024,
+                          ("const", 640), ("lognormal", 200.0, 1.0),
+                          note="128 prompts x G=16, 16/2 heads, prefix 576 visual + 64 text"),
+}
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """A copy of ``w`` with some fields replaced (reduced-size parity cases)."""
+    return replace(w, **kw)
+
+
+def _draw_lens(rng: np.random.Generator, kind: tuple, n: int, cap: int) -> np.ndarray:
+    if kind[0] == "const":
+        lens = np.full(n, kind[1], dtype=np.int64)
+    elif kind[0] == "uniform":                      # integers, both ends inclusive
+        lens = rng.integers(0, kind[1] + 1, size=n)
+    elif kind[0] == "lognormal":                    # median * exp(sigma z), rounded, clipped
+        z = rng.standard_normal(n)
+        lens = np.rint(np.exp(math.log(kind[1]) + kind[2] * z)).astype(np.int64)
+    elif kind[0] == "agentic":                      # n_img x (img_tokens + U{lo..hi} text)
+        _, n_img, img, lo, hi = kind
+        lens = n_img * img + rng.integers(lo, hi + 1, size=(n, n_img)).sum(axis=1)
+    else:
+        raise ValueError(kind)
+    return np.clip(lens, 0, cap).astype(np.int32)
+
+
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even fp32 -> bf16, returned as uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+_CHUNK = 1 << 23  # elements per independently seeded chunk
+
+
+def _normal_tensor(seed: int, tensor_id: int, shape, dtype: str, gain: float, threads: int):
+    """N(0,1)*gain tensor; each 8M-element chunk has its own child seed so the
+    values do not depend on how many threads filled it."""
+    n = int(np.prod(shape, dtype=np.int64))
+    out = np.empty(n, dtype=np.float32 if dtype == "f32" else np.uint16)
+
+    def fill(ci: int):
+        lo, hi = ci * _CHUNK, min(n, (ci + 1) * _CHUNK)
+        g = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, tensor_id, ci])))
+        x = g.standard_normal(hi - lo, dtype=np.float32)
+        if gain != 1.0:
+            x *= np.float32(gain)
+        out[lo:hi] = x if dtype == "f32" else f32_to_bf16_bits(x)
+
+    n_chunks = (n + _CHUNK - 1) // _CHUNK
+    if n_chunks <= 1 or threads <= 1:
+        for ci in range(n_chunks):
+            fill(ci)
+    else:
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            list(ex.map(fill, range(n_chunks)))
+    return out.reshape(shape)
+
+
+def make_inputs(w: Workload, threads: int = 8) -> dict:
+    """Draw one batch: lengths first, then q, k_prefix, v_prefix, k_suffix, v_suffix.
+
+    Every row of the KV buffers is filled (also rows beyond the drawn lengths)
+    so that a kernel that reads past a length is caught by the parity check.
+    """
+    rng = np.random.default_rng(w.seed)
+    prefix_lens = _draw_lens(rng, w.prefix, w.P, w.Lp_cap)
+    suffix_lens = _draw_lens(rng, w.suffix, w.B, w.Ls_cap)
+    t = lambda i, shape, gain=1.0: _normal_tensor(w.seed, i, shape, w.dtype, gain, threads)
+    return {
+        "prefix_lens": prefix_lens,
+        "suffix_lens": suffix_lens,
+        "q": t(0, (w.B, w.Hq, w.d), w.q_gain),
+        "k_prefix": t(1, (w.P, w.Hkv, w.Lp_cap, w.d)),
+        "v_prefix": t(2, (w.P, w.Hkv, w.Lp_cap, w.d)),
+        "k_suffix": t(3, (w.B, w.Hkv, w.Ls_cap, w.d)),
+        "v_suffix": t(4, (w.B, w.Hkv, w.Ls_cap, w.d)),
+    }
+
+
+def algorithmic_bytes(w: Workload, prefix_lens, suffix_lens) -> dict:
+    """Bytes one decode step has to move, from the realised lengths: each
+    prompt's prefix K/V once, each sequence's own suffix K/V once, q in,
+    out (fp32) and lse (fp32) out, and the two length arrays."""
+    row = w.Hkv * 2 * w.d * w.elem_bytes                      # K+V bytes per token, all KV heads
+    prefix = int(np.sum(prefix_lens, dtype=np.int64)) * row
+    suffix = int(np.sum(suffix_lens, dtype=np.int64)) * row
+    io = w.B * w.Hq * w.d * w.elem_bytes + w.B * w.Hq * w.d * 4 + w.B * w.Hq * 4 + 4 * (w.P + w.B)
+    return {"prefix": prefix, "suffix": suffix, "io": io, "total": prefix + suffix + io}
