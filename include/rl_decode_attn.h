@@ -1,0 +1,148 @@
+/*
+ * rl_decode_attn -- shared-prefix grouped-query decode attention for
+ * GRPO-style rollouts, for AMD MI355X (gfx950).  C ABI, no C++ or framework
+ * types in any signature.
+ *
+ * What one call computes.  The paper casts generation as an MDP whose state is
+ * the whole sequence so far, whose action is one token and whose transition
+ * appends it (Sec. 2.2; Sec. 3.1 "The MDP of RLLaVA", items (1)-(4)); the
+ * initial state s_0 = (x_0, y_0) is an image part plus a text part (text under
+ * Eq. 6), and for every prompt the old policy samples a group of K
+ * trajectories from that same s_0 (Algorithm 1, rollout steps; Sec. 3.2.2
+ * "Sampling stage"; Sec. 5.1: 4-8 responses per prompt).  One call is one
+ * decode action of all B = P*G live trajectories for one attention layer:
+ * sequence b = p*G + g has one query token, and its keys are the P-shared
+ * prompt prefix of prompt p followed by its own generated suffix.  The paper
+ * prints no attention formula; the call evaluates the scaled dot-product
+ * softmax attention with grouped-query heads of the policy models it names
+ * (Sec. 5.1 "Models"):
+ *
+ *   j = h / (Hq/Hkv)
+ *   s_n = scale * <q[b,h,:], K_n>,   K_n/V_n = prefix[p,j,n,:]        n <  Lp[p]
+ *                                             suffix[b,j,n-Lp[p],:]   n >= Lp[p]
+ *   lse[b,h] = ln sum_n exp(s_n)            (natural log; -inf if no key)
+ *   out[b,h,:] = sum_n exp(s_n - lse) V_n   (0 if no key)
+ *
+ * No causal mask is applied (the single query sees every resident key; the
+ * caller has already appended the current token's K/V and counted it in
+ * suffix_lens).  Positional rotation of q and K happens before the call.
+ *
+ * How it is computed: the prefix K/V of a prompt is read from HBM once and
+ * reused by all G samples and all Hq/Hkv query heads of a KV group; each
+ * sequence's suffix is streamed once; partial (o, lse) results of key ranges
+ * are merged by a log-sum-exp combine.  The result is exact up to fp32
+ * rounding order (bf16 inputs: softmax weights are rounded to bf16 before the
+ * value contraction, accumulation is fp32).
+ */
+#ifndef RL_DECODE_ATTN_H
+#define RL_DECODE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Element type of q, k_*, v_*.  out and lse are always fp32. */
+typedef enum { RLDA_F32 = 0, RLDA_BF16 = 1 } rlda_dtype;
+
+/* Kernel selection. */
+typedef enum {
+  RLDA_ALGO_AUTO = 0,      /* shared-prefix MFMA path when the shape allows it, else SIMPLE */
+  RLDA_ALGO_SIMPLE = 1,    /* one wavefront per (sequence, query head), no sharing, no split */
+  RLDA_ALGO_SHARED = 2     /* force the shared-prefix path; RLDA_ERR_UNSUPPORTED if not possible */
+} rlda_algo;
+
+/* Return codes. */
+enum {
+  RLDA_OK = 0,
+  RLDA_ERR_INVALID = -1,      /* NULL descriptor / required pointer NULL / negative size        */
+  RLDA_ERR_UNSUPPORTED = -2,  /* d not in {64,128}, Hq % Hkv != 0, unknown dtype or algo, ...   */
+  RLDA_ERR_WORKSPACE = -3,    /* workspace NULL or smaller than rl_decode_attn_workspace_bytes  */
+  RLDA_ERR_STRUCT_SIZE = -4,  /* struct_size != sizeof(rlda_desc) of this library version       */
+  RLDA_ERR_LAUNCH = -5        /* the HIP runtime reported an error when enqueuing               */
+};
+
+/*
+ * Problem descriptor.  All tensors are contiguous, row-major, DEVICE memory
+ * unless noted.  The library owns nothing: every pointer is borrowed until the
+ * enqueued work has run on `stream`; inputs are never written; the contents of
+ * `workspace` are undefined afterwards.
+ */
+typedef struct {
+  uint32_t struct_size;        /* = sizeof(rlda_desc)                                            */
+  int32_t  dtype;              /* rlda_dtype                                                     */
+  int32_t  algo;               /* rlda_algo                                                      */
+  int32_t  P, G;               /* prompts, samples per prompt; sequence b = p*G + g              */
+  int32_t  Hq, Hkv, d;         /* query heads, KV heads (Hq % Hkv == 0), head dim (64 or 128)    */
+  int32_t  Lp_cap, Ls_cap;     /* row capacity of the prefix / suffix KV buffers (>= 0)          */
+  float    scale;              /* multiplies <q,k> before the softmax                            */
+  const void*    q;            /* [B, Hq, d]                                                     */
+  const void*    k_prefix;     /* [P, Hkv, Lp_cap, d]   (may be NULL if Lp_cap == 0)             */
+  const void*    v_prefix;     /* [P, Hkv, Lp_cap, d]                                            */
+  const int32_t* prefix_lens;  /* [P]  valid prefix rows per prompt; clamped to [0, Lp_cap]      */
+  const void*    k_suffix;     /* [B, Hkv, Ls_cap, d]   (may be NULL if Ls_cap == 0)             */
+  const void*    v_suffix;     /* [B, Hkv, Ls_cap, d]                                            */
+  const int32_t* suffix_lens;  /* [B]  valid suffix rows per sequence; clamped to [0, Ls_cap]    */
+  float*   out;                /* [B, Hq, d] fp32                                                */
+  float*   lse;                /* [B, Hq]    fp32, natural log; may be NULL                      */
+  void*    workspace;          /* device scratch, 256-byte aligned, may be NULL if 0 bytes needed */
+  size_t   workspace_bytes;
+} rlda_desc;
+
+/*
+ * Enqueue one decode-attention step on `hip_stream` (a hipStream_t passed as
+ * void*; NULL = the default stream).  Asynchronous: never synchronises, never
+ * reads device memory from the host, never allocates.  Lengths live on the
+ * device, so out-of-range values cannot be rejected here; the kernels clamp
+ * them to [0, cap].  Rows at or beyond a length are never used and may hold
+ * anything (including NaN).  Returns RLDA_OK or a negative RLDA_ERR_* code; on
+ * error nothing has been enqueued.  Results are bit-reproducible from call to
+ * call for identical inputs.
+ */
+int rl_decode_attn(const rlda_desc* desc, void* hip_stream);
+
+/*
+ * Bytes of device workspace rl_decode_attn needs for this descriptor (only the
+ * shape fields, dtype and algo are read; no pointer is dereferenced, no device
+ * is touched).  Returns 0 if none is needed or if the descriptor is invalid
+ * (rl_decode_attn reports the reason).
+ */
+size_t rl_decode_attn_workspace_bytes(const rlda_desc* desc);
+
+/*
+ * The kernel family rl_decode_attn would run for this descriptor:
+ * RLDA_ALGO_SIMPLE or RLDA_ALGO_SHARED, or a negative RLDA_ERR_* code.
+ * Pure host function.
+ */
+int rl_decode_attn_plan(const rlda_desc* desc);
+
+/* Static, NUL-terminated description of a return code. */
+const char* rl_decode_attn_strerror(int code);
+
+/*
+ * Text of the HIP runtime status of the calling thread's most recent
+ * rl_decode_attn / rl_lse_combine enqueue (for diagnosing RLDA_ERR_LAUNCH).
+ */
+const char* rl_decode_attn_last_hip_error(void);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int rl_decode_attn_version(void);
+
+/*
+ * The log-sum-exp combine step on its own (merge of split-softmax partials):
+ * for each of n_rows rows, given n_parts partial results over disjoint key
+ * sets, o_parts [n_parts, n_rows, d] fp32 (each already normalised) and
+ * lse_parts [n_parts, n_rows] fp32 (-inf marks an empty part),
+ *   lse = ln sum_i exp(lse_i),  out = sum_i exp(lse_i - lse) * o_i,
+ * with out = 0, lse = -inf when every part is empty.  All pointers are device
+ * memory; lse may be NULL.  d must be 64 or 128.  Asynchronous on `hip_stream`.
+ */
+int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts,
+                   int64_t n_rows, int32_t d, float* out, float* lse, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

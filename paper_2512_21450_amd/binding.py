@@ -1,0 +1,188 @@
+"""Thin Python binding of the C-ABI library (argument marshalling only).
+
+Every step of the computation runs in the HIP kernels behind
+``librl_decode_attn.so``; PyTorch is used for device memory and streams.
+There is no CPU fallback: importing this module raises if the library has not
+been built (``python -m paper_2512_21450_amd.build``).
+
+Function names mirror ``include/rl_decode_attn.h``.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+# torch first: it brings its own HIP runtime (same soname as the system one), and
+# the library must bind to the runtime that owns torch's streams and allocations.
+import torch  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librl_decode_attn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build the HIP library first (python -m paper_2512_21450_amd.build). "
+        "There is no fallback path.")
+
+_lib = ctypes.CDLL(LIB_PATH)
+
+RLDA_F32, RLDA_BF16 = 0, 1
+RLDA_ALGO_AUTO, RLDA_ALGO_SIMPLE, RLDA_ALGO_SHARED = 0, 1, 2
+RLDA_OK, RLDA_ERR_INVALID, RLDA_ERR_UNSUPPORTED = 0, -1, -2
+RLDA_ERR_WORKSPACE, RLDA_ERR_STRUCT_SIZE, RLDA_ERR_LAUNCH = -3, -4, -5
+
+
+class rlda_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("algo", ctypes.c_int32),
+        ("P", ctypes.c_int32), ("G", ctypes.c_int32),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("Lp_cap", ctypes.c_int32), ("Ls_cap", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("q", ctypes.c_void_p),
+        ("k_prefix", ctypes.c_void_p), ("v_prefix", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
+        ("k_suffix", ctypes.c_void_p), ("v_suffix", ctypes.c_void_p), ("suffix_lens", ctypes.c_void_p),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+_dp = ctypes.POINTER(rlda_desc)
+_lib.rl_decode_attn.restype = ctypes.c_int
+_lib.rl_decode_attn.argtypes = [_dp, ctypes.c_void_p]
+_lib.rl_decode_attn_workspace_bytes.restype = ctypes.c_size_t
+_lib.rl_decode_attn_workspace_bytes.argtypes = [_dp]
+_lib.rl_decode_attn_plan.restype = ctypes.c_int
+_lib.rl_decode_attn_plan.argtypes = [_dp]
+_lib.rl_decode_attn_strerror.restype = ctypes.c_char_p
+_lib.rl_decode_attn_strerror.argtypes = [ctypes.c_int]
+_lib.rl_decode_attn_version.restype = ctypes.c_int
+_lib.rl_decode_attn_version.argtypes = []
+_lib.rl_decode_attn_last_hip_error.restype = ctypes.c_char_p
+_lib.rl_decode_attn_last_hip_error.argtypes = []
+_lib.rl_lse_combine.restype = ctypes.c_int
+_lib.rl_lse_combine.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32,
+                                ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+
+
+class RldaError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        detail = f" ({rl_decode_attn_last_hip_error()})" if code == RLDA_ERR_LAUNCH else ""
+        super().__init__(f"rl_decode_attn error {code}: {rl_decode_attn_strerror(code)}{detail}")
+
+
+def make_desc(dtype, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, scale, algo=RLDA_ALGO_AUTO, **ptrs) -> rlda_desc:
+    """Fill a descriptor from plain integers; pointer fields default to NULL."""
+    ds = rlda_desc()
+    ds.struct_size = ctypes.sizeof(rlda_desc)
+    ds.dtype, ds.algo = dtype, algo
+    ds.P, ds.G, ds.Hq, ds.Hkv, ds.d, ds.Lp_cap, ds.Ls_cap = P, G, Hq, Hkv, d, Lp_cap, Ls_cap
+    ds.scale = scale
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_decode_attn_version() -> int:
+    return _lib.rl_decode_attn_version()
+
+
+def rl_decode_attn_strerror(code: int) -> str:
+    return _lib.rl_decode_attn_strerror(code).decode()
+
+
+def rl_decode_attn_last_hip_error() -> str:
+    return _lib.rl_decode_attn_last_hip_error().decode()
+
+
+def rl_decode_attn_workspace_bytes(desc: rlda_desc) -> int:
+    return _lib.rl_decode_attn_workspace_bytes(ctypes.byref(desc))
+
+
+def rl_decode_attn_plan(desc: rlda_desc) -> int:
+    return _lib.rl_decode_attn_plan(ctypes.byref(desc))
+
+
+def rl_decode_attn_raw(desc: rlda_desc, stream_handle=None) -> int:
+    """Direct call; returns the C return code."""
+    return _lib.rl_decode_attn(ctypes.byref(desc), stream_handle)
+
+
+def _torch_dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return RLDA_F32
+    if t.dtype == torch.bfloat16:
+        return RLDA_BF16
+    raise TypeError(f"q/k/v must be float32 or bfloat16, got {t.dtype}")
+
+
+def desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
+                      out, lse=None, workspace=None, algo=RLDA_ALGO_AUTO) -> rlda_desc:
+    """Descriptor over torch device tensors (shapes as in the header)."""
+    B, Hq, d = q.shape
+    P, Hkv, Lp_cap, _ = k_prefix.shape
+    Ls_cap = k_suffix.shape[2]
+    if B != P * G or k_suffix.shape[0] != B or k_suffix.shape[1] != Hkv:
+        raise ValueError("inconsistent shapes")
+    for t in (q, k_prefix, v_prefix, k_suffix, v_suffix, prefix_lens, suffix_lens, out):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    code = _torch_dtype_code(q)
+    for t in (k_prefix, v_prefix, k_suffix, v_suffix):
+        if _torch_dtype_code(t) != code:
+            raise TypeError("q/k/v dtypes differ")
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    return make_desc(code, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale), algo,
+                     q=ptr(q), k_prefix=ptr(k_prefix), v_prefix=ptr(v_prefix), prefix_lens=ptr(prefix_lens),
+                     k_suffix=ptr(k_suffix), v_suffix=ptr(v_suffix), suffix_lens=ptr(suffix_lens),
+                     out=ptr(out), lse=ptr(lse), workspace=ptr(workspace),
+                     workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+
+
+def rl_decode_attn(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
+                   out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None):
+    """One decode-attention step on torch device tensors; returns (out, lse).
+
+    Allocates out/lse/workspace with torch when they are not passed in.  The
+    call is asynchronous on ``stream`` (default: torch's current stream).
+    """
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_decode_attn needs device tensors; there is no CPU path")
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    ds = desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
+                           out, lse, workspace, algo)
+    if workspace is None:
+        need = rl_decode_attn_workspace_bytes(ds)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            ds.workspace, ds.workspace_bytes = workspace.data_ptr(), need
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_decode_attn(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse
+
+
+def rl_lse_combine(o_parts, lse_parts, out=None, lse=None, stream=None):
+    """Merge partials o_parts [n_parts, n_rows, d], lse_parts [n_parts, n_rows] (fp32 device tensors)."""
+    import torch
+    n_parts, n_rows, d = o_parts.shape
+    if out is None:
+        out = torch.empty((n_rows, d), dtype=torch.float32, device=o_parts.device)
+    if lse is None:
+        lse = torch.empty((n_rows,), dtype=torch.float32, device=o_parts.device)
+    s = stream if stream is not None else torch.cuda.current_stream(o_parts.device)
+    rc = _lib.rl_lse_combine(o_parts.data_ptr(), lse_parts.data_ptr(), n_parts, n_rows, d,
+                             out.data_ptr(), lse.data_ptr(), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse

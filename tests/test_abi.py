@@ -1,0 +1,104 @@
+"""The C-ABI library without a GPU: it loads, exports what the header
+declares, and every host-side validation path returns its documented code
+without launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_21450_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    inc = os.path.join(ROOT, "include")
+    for f in sorted(os.listdir(inc)):
+        if not f.endswith(".h"):
+            continue
+        src = open(os.path.join(inc, f)).read()
+        src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+        names += re.findall(r"\b(rl_[a-z0-9_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"rl_decode_attn", "rl_decode_attn_workspace_bytes", "rl_decode_attn_plan",
+            "rl_decode_attn_strerror", "rl_decode_attn_version", "rl_lse_combine"} <= set(names)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/ but not exported"
+
+
+def test_version_and_strerror():
+    assert B.rl_decode_attn_version() >= 100
+    for code in (0, -1, -2, -3, -4, -5):
+        assert B.rl_decode_attn_strerror(code) not in ("", "unknown error code")
+    assert B.rl_decode_attn_strerror(-99) == "unknown error code"
+
+
+def good(**kw):
+    args = dict(dtype=B.RLDA_BF16, P=2, G=4, Hq=8, Hkv=2, d=128, Lp_cap=64, Ls_cap=64, scale=0.1)
+    args.update(kw)
+    return B.make_desc(**args)
+
+
+def test_descriptor_layout_matches_the_header():
+    # 11 four-byte fields, padding to 8, 9 pointers, pointer + size_t
+    assert ctypes.sizeof(B.rlda_desc) == 48 + 9 * 8 + 16
+    assert B.rlda_desc.q.offset == 48 and B.rlda_desc.workspace_bytes.offset == 48 + 10 * 8
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), B.RLDA_ERR_UNSUPPORTED),
+    (dict(d=256), B.RLDA_ERR_UNSUPPORTED),
+    (dict(Hq=7, Hkv=2), B.RLDA_ERR_UNSUPPORTED),
+    (dict(dtype=5), B.RLDA_ERR_UNSUPPORTED),
+    (dict(algo=9), B.RLDA_ERR_UNSUPPORTED),
+    (dict(P=-1), B.RLDA_ERR_INVALID),
+    (dict(Lp_cap=-3), B.RLDA_ERR_INVALID),
+    (dict(Hkv=0), B.RLDA_ERR_INVALID),
+    (dict(dtype=B.RLDA_F32, algo=B.RLDA_ALGO_SHARED), B.RLDA_ERR_UNSUPPORTED),
+])
+def test_shape_errors(kw, code):
+    ds = good(**kw)
+    assert B.rl_decode_attn_plan(ds) == code
+    assert B.rl_decode_attn_raw(ds) == code
+    assert B.rl_decode_attn_workspace_bytes(ds) == 0
+
+
+def test_struct_size_mismatch_and_null_descriptor():
+    ds = good()
+    ds.struct_size = 8
+    assert B.rl_decode_attn_raw(ds) == B.RLDA_ERR_STRUCT_SIZE
+    assert B._lib.rl_decode_attn(None, None) == B.RLDA_ERR_INVALID
+    assert B._lib.rl_decode_attn_workspace_bytes(None) == 0
+
+
+def test_null_pointers_are_rejected_before_any_launch():
+    fake = 0x1000  # never dereferenced on the host; the call must fail before enqueuing
+    full = dict(q=fake, k_prefix=fake, v_prefix=fake, prefix_lens=fake, k_suffix=fake, v_suffix=fake,
+                suffix_lens=fake, out=fake)
+    for missing in full:
+        ptrs = {k: v for k, v in full.items() if k != missing}
+        ds = good(algo=B.RLDA_ALGO_SIMPLE, **ptrs)
+        assert B.rl_decode_attn_raw(ds) == B.RLDA_ERR_INVALID, missing
+
+
+def test_plan_and_workspace_query():
+    assert B.rl_decode_attn_plan(good(algo=B.RLDA_ALGO_SIMPLE)) == B.RLDA_ALGO_SIMPLE
+    assert B.rl_decode_attn_workspace_bytes(good(algo=B.RLDA_ALGO_SIMPLE)) == 0
+    assert B.rl_decode_attn_plan(good(dtype=B.RLDA_F32, d=64)) == B.RLDA_ALGO_SIMPLE
+    # empty batch is a successful no-op that touches no device
+    assert B.rl_decode_attn_raw(good(P=0)) == B.RLDA_OK
+
+
+def test_lse_combine_argument_checks():
+    f = B._lib.rl_lse_combine
+    assert f(None, None, 2, 4, 96, None, None, None) == B.RLDA_ERR_UNSUPPORTED
+    assert f(None, None, -1, 4, 128, None, None, None) == B.RLDA_ERR_INVALID
+    assert f(None, None, 2, 4, 128, 0x1000, None, None) == B.RLDA_ERR_INVALID
+    assert f(None, None, 2, 0, 128, None, None, None) == B.RLDA_OK
