@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Throughput of one decode-attention step (the whole hot path) on one MI355X.
+
+A step is one ``rl_decode_attn`` call over one batch of synthetic rollout
+state: every sequence of every GRPO group issues one query token against its
+prompt's shared prefix and its own suffix.  Inputs are resident in HBM before
+the timed region; several copies of the KV tensors are rotated so that no step
+finds its inputs in the memory-side cache.
+
+Prints ONE JSON line: query-tokens/s, the HBM roofline of the kernel (bytes the
+method must move / kernel time from HIP events on the launch stream), and the
+fp64 CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="vlm7b", help="tiny | vlm3b | vlm7b | agentic | highbatch")
+    ap.add_argument("--algo", default="auto", choices=["auto", "simple", "shared"])
+    ap.add_argument("--sets", type=int, default=3, help="rotating copies of the KV tensors")
+    ap.add_argument("--cpu-seqs", type=int, default=32, help="sequences in the CPU-oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is a single-GPU kernel library; only --gpus 1 is supported "
+              "(the path shards by prompt group with no exchange, nothing to measure across GPUs here)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_21450_amd import binding as B
+    from paper_2512_21450_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = wl.WORKLOADS[args.workload]
+    algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
+
+    x = wl.make_inputs(w, threads=16)
+    ab = wl.algorithmic_bytes(w, x["prefix_lens"], x["suffix_lens"])
+
+    def dev_t(a):
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+        return torch.from_numpy(a).to(dev)
+
+    base = {k: dev_t(v) for k, v in x.items()}
+    sets = [base] + [{k: (v.clone() if k.startswith(("k_", "v_")) else v) for k, v in base.items()}
+                     for _ in range(max(args.sets, 1) - 1)]
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
+    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device=dev)
+    descs = []
+    ws = None
+    for s in sets:
+        ds = B.desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_suffix"],
+                                 s["v_suffix"], s["suffix_lens"], w.scale, w.G, out, lse, None, algo)
+        if ws is None:
+            need = B.rl_decode_attn_workspace_bytes(ds)
+            ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+        ds.workspace, ds.workspace_bytes = ws.data_ptr(), ws.numel()
+        descs.append(ds)
+    plan = B.rl_decode_attn_plan(descs[0])
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def step(i):
+        rc = B.rl_decode_attn_raw(descs[i % len(descs)], sh)
+        if rc != 0:
+            raise B.RldaError(rc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record(stream)
+        step(i)
+        ev[i][1].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    value = w.B / (ms_per_step * 1e-3)
+
+    # sanity: the timed configuration still matches the oracle on sampled rows
+    rng = np.random.default_rng(0)
+    rows = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.Hq, 64)], 1).astype(np.int32)
+    from oracle import ref
+    ro, rl = ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
+                                 x["v_suffix"], x["suffix_lens"], w.scale, w.G, rows=rows)
+    step(0)
+    torch.cuda.synchronize()
+    o, l = out.cpu().numpy(), lse.cpu().numpy()
+    tol_o, tol_l = (1e-5, 1e-5) if w.dtype == "f32" else (1e-2, 1e-3)
+    err_o = max(float(np.abs(o[b, h] - ro[b, h]).max()) for b, h in rows)
+    fin = [(b, h) for b, h in rows if np.isfinite(rl[b, h])]
+    err_l = max([abs(float(l[b, h]) - rl[b, h]) for b, h in fin], default=0.0)
+    parity_ok = bool(err_o <= tol_o and err_l <= tol_l)
+
+    # CPU baseline: the oracle as it stands on a bounded sample (whole sequences, all heads)
+    cpu = None
+    if args.cpu_seqs > 0:
+        n = min(args.cpu_seqs, w.B)
+        seqs = np.linspace(0, w.B - 1, n).astype(np.int32)
+        rws = np.stack([np.repeat(seqs, w.Hq), np.tile(np.arange(w.Hq, dtype=np.int32), n)], 1)
+        c0 = time.perf_counter()
+        _, _, used = ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
+                                         x["v_suffix"], x["suffix_lens"], w.scale, w.G, rows=rws,
+                                         return_threads=True)
+        c1 = time.perf_counter()
+        cpu = {"value": n / (c1 - c0), "unit": "query-tokens/s", "cores": int(used), "kind": "oracle",
+               "sample": f"{n} of {w.B} sequences (all {w.Hq} heads, evenly spaced), {c1 - c0:.2f} s"}
+
+    kern_us = float(kern_ms.mean() * 1e3)
+    achieved = ab["total"] / (kern_us * 1e-6) / 1e9
+    res = {
+        "metric": "decode-attn query-tokens/sec and achieved HBM GB/s (% of MI355X peak), 7B shape",
+        "value": value, "unit": "query-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}; suffix {w.suffix}", "P": w.P, "G": w.G, "Hq": w.Hq,
+                   "Hkv": w.Hkv, "d": w.d, "algo": {1: "simple", 2: "shared"}.get(plan, str(plan)),
+                   "kv_sets_rotated": len(sets),
+                   "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
+                   "mean_prefix_len": float(x["prefix_lens"].mean())},
+        "achieved_GBps_whole_step": ab["total"] / (ms_per_step * 1e-3) / 1e9,
+        "pct_of_hbm_peak_whole_step": 100.0 * ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_bytes": ab,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
+                     "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3)},
+        "cpu_baseline": cpu,
+        "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
+    }
+    print(json.dumps(res))
+    if not parity_ok:
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()
