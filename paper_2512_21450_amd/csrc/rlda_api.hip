@@ -2,6 +2,9 @@
 // Validation and the workspace/plan queries are pure host code and work
 // without a GPU; only rl_decode_attn / rl_lse_combine touch the HIP runtime.
 #include "rlda_internal.h"
+#include "rlda_sched.h"
+
+#include <vector>
 
 namespace {
 
@@ -92,6 +95,67 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
                                             static_cast<hipStream_t>(hip_stream));
   g_last_hip_error = e;
   return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
+}
+
+int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t Lp_cap, int32_t Ls_cap,
+                                       const int32_t* prefix_lens, const int32_t* suffix_lens,
+                                       int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
+                                       int64_t* n_parts) {
+  using namespace rlda;
+  if (P < 0 || G < 0 || Hkv <= 0 || !prefix_lens || !suffix_lens || !n_parts) return RLDA_ERR_INVALID;
+  const int B = P * G;
+  std::vector<int> X(P + B + 2, 0);
+  auto tp = [&](int p) { return ceil_div(clampi(prefix_lens[p], 0, Lp_cap), TK); };
+  auto ts = [&](int b) { return ceil_div(clampi(suffix_lens[b], 0, Ls_cap), TK); };
+  for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
+  for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
+  const int cumP = X[P];
+  const Sched sc = make_sched(cumP * Hkv, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, N_WG);
+  int64_t nr = 0, np = 0;
+  auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
+    if (runs && nr < runs_cap) {
+      int32_t* o = runs + nr * 8;
+      o[0] = kind; o[1] = major; o[2] = j; o[3] = t0; o[4] = n; o[5] = w; o[6] = v; o[7] = slot;
+    }
+    ++nr;
+  };
+  for (int w = 0; w < N_WG; ++w) {               // the partial kernel's walk
+    int ilo, ihi, klo, khi;
+    wg_prefix_range(sc, w, ilo, ihi);
+    wg_suffix_range(sc, w, klo, khi);
+    if (ilo < ihi) {
+      int p, j, t;
+      locate(X.data(), P, Hkv, ilo, p, j, t);
+      for_each_run(ilo, ihi, P, Hkv, p, j, t, tp,
+                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * Hkv + jj + w); });
+    }
+    for (int v = 0; v < WG_WAVES; ++v) {
+      int ka, kb;
+      wave_suffix_range(klo, khi, v, ka, kb);
+      if (ka >= kb) continue;
+      int b, j, t;
+      locate(X.data() + P, B, Hkv, ka + cumP * Hkv, b, j, t);
+      for_each_run(ka, kb, B, Hkv, b, j, t, ts, [&](int bb, int jj, int t0, int n) {
+        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * w + v);
+      });
+    }
+  }
+  auto put_part = [&](int kind, int major, int j, int w, int v, int slot) {
+    if (parts && np < parts_cap) {
+      int32_t* o = parts + np * 6;
+      o[0] = kind; o[1] = major; o[2] = j; o[3] = w; o[4] = v; o[5] = slot;
+    }
+    ++np;
+  };
+  for (int p = 0; p < P; ++p)                    // the combine kernel's enumeration
+    for (int j = 0; j < Hkv; ++j)
+      for_each_prefix_part(sc, X.data(), Hkv, p, j, [&](int w) { put_part(0, p, j, w, -1, p * Hkv + j + w); });
+  for (int b = 0; b < B; ++b)
+    for (int j = 0; j < Hkv; ++j)
+      for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j,
+                           [&](int w, int v) { put_part(1, b, j, w, v, b * Hkv + j + WG_WAVES * w + v); });
+  *n_parts = np;
+  return nr;
 }
 
 }  // extern "C"

@@ -1,8 +1,459 @@
-// Shared-prefix MFMA path (placeholder until the kernels land).
+// Shared-prefix decode attention on gfx950 matrix cores (bf16 in, fp32 accumulate, d = 128).
+//
+// Two kernels per call:
+//   partial_kernel  walks the static tile partition of rlda_sched.h.  Prefix tiles
+//                   (the prompt s_0 shared by the K sampled trajectories of a group,
+//                   Algorithm 1 / Sec. 3.2.2 of the paper) are staged once in LDS per
+//                   workgroup and used by all G * Hq/Hkv query rows of the KV group;
+//                   suffix tiles (each trajectory's own generated tokens, Sec. 3.1
+//                   transition s' = (s, a)) are streamed by single wavefronts.
+//   combine_kernel  merges the partial (o, lse) of every (sequence, head) by
+//                   log-sum-exp and writes out / lse.
+//
+// Tile math (one wavefront, 16 query rows, 32 keys): scores are produced
+// transposed, S^T = K_tile * Q^T, with v_mfma_f32_16x16x32_bf16 (A = 16 keys x 32
+// dims read from LDS, B = Q^T held in registers).  In that accumulator layout a
+// lane owns one query row and 4 keys per 16-key half, which is exactly the
+// B-operand layout of the second contraction O^T += V_tile^T * P^T, so the
+// probabilities go from accumulator to operand with a bf16 convert and no
+// cross-lane traffic.  V^T comes from LDS through ds_read_b64_tr_b16.  The online
+// softmax needs one 4-lane max per tile (two xor-shuffles); row sums stay per
+// lane until the partial is written.
 #include "rlda_internal.h"
+#include "rlda_sched.h"
 
 namespace rlda {
-bool shared_supported(const rlda_desc&) { return false; }
-size_t shared_workspace_bytes(const rlda_desc&) { return 0; }
-hipError_t launch_shared(const rlda_desc&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+constexpr int D = 128;
+constexpr int ROWB = D * 2;                       // bytes per K/V row
+constexpr int TILE_B = TK * ROWB;                 // 8 KB: one K or V tile
+constexpr int STAGE_B = 2 * TILE_B;               // K tile + V tile
+constexpr int NTHREADS = 64 * WG_WAVES;
+constexpr int LDS_BYTES = WG_WAVES * STAGE_B;     // 64 KB -> two workgroups per CU
+constexpr int MAX_SCAN = LDS_BYTES / 4;           // ints of LDS available to the length scan
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct SharedParams {
+  const char* q; const char* kp; const char* vp; const char* ks; const char* vs;
+  const int32_t* plens; const int32_t* slens;
+  float* out; float* lse;
+  int32_t* cum;           // [P + B + 1] exclusive scan of tile counts (prompts, then sequences)
+  float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
+  float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
+  int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
+  int wP, n_wg;
+  float c;                // scale * log2(e): scores are kept in base 2
+};
+
+template <int NT>
+struct WaveState {
+  f32x4 O[NT][8];         // O^T accumulators: [row tile][16-column tile], lane (row, g) holds cols 16ct+4g..+3
+  float m[NT];            // running max (base-2 scores), equal in the 4 lanes of a row
+  float l[NT];            // this lane's share of the row sum, exact fp32 weights (for lse)
+  float lr[NT];           // same with the bf16-rounded weights (normalises O)
+};
+
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// 16-byte chunk `chunk` of tile row `row` lives at this byte offset inside a K / V tile in LDS.
+// K is read 16 rows x one chunk per wavefront instruction, V 4 rows x two adjacent chunks per
+// 16 lanes; the xor patterns spread either access over all banks.
+__device__ __forceinline__ int k_off(int row, int chunk) { return row * ROWB + ((chunk ^ (row & 15)) << 4); }
+__device__ __forceinline__ int v_off(int row, int chunk) { return row * ROWB + ((chunk ^ ((row & 7) << 1)) << 4); }
+
+#define RLDA_LDS(T, p) ((__attribute__((address_space(3))) T*)(p))
+__device__ __forceinline__ bf16x8 lds_ld128(const char* p) { return *RLDA_LDS(const bf16x8, p); }
+__device__ __forceinline__ void lds_st128(char* p, u32x4 v) { *RLDA_LDS(u32x4, p) = v; }
+__device__ __forceinline__ s16x4 lds_ld_tr16(const char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(RLDA_LDS(s16x4, const_cast<char*>(p)));
+}
+
+template <int NT>
+__device__ __forceinline__ void init_state(WaveState<NT>& st) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    st.m[nt] = -INFINITY; st.l[nt] = 0.f; st.lr[nt] = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+}
+
+// One 32-key tile (K at Kl, V at Vl in LDS, first `nvalid` keys real) against NT blocks of 16 query rows.
+template <int NT>
+__device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, int nvalid, const bf16x8 (&qf)[NT][4],
+                                             WaveState<NT>& st, float c, int lane) {
+  const int m16 = lane & 15, g = lane >> 4;
+  f32x4 s0[NT], s1[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) { s0[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    const int off = k_off(m16, 4 * ks + g);
+    const bf16x8 a0 = lds_ld128(Kl + off);
+    const bf16x8 a1 = lds_ld128(Kl + off + 16 * ROWB);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      s0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qf[nt][ks], s0[nt], 0, 0, 0);
+      s1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qf[nt][ks], s1[nt], 0, 0, 0);
+    }
+  }
+  bf16x8 pb[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float sv[8];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      sv[x] = (4 * g + x < nvalid) ? s0[nt][x] * c : -INFINITY;
+      sv[4 + x] = (16 + 4 * g + x < nvalid) ? s1[nt][x] * c : -INFINITY;
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));          // finite: key 0 of the tile is always real
+    const float m_new = fmaxf(st.m[nt], tmax);
+    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new);   // first tile: exp2(-inf) = 0
+    float se = 0.f, sr = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const float pe = __builtin_amdgcn_exp2f(sv[x] - m_new);      // masked keys: 0
+      const __bf16 pr = static_cast<__bf16>(pe);
+      pb[nt][x] = pr;
+      se += pe;
+      sr += static_cast<float>(pr);
+    }
+    st.l[nt] = st.l[nt] * alpha + se;
+    st.lr[nt] = st.lr[nt] * alpha + sr;
+    st.m[nt] = m_new;
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
+    }
+  }
+  // lane (m16, g) of a 16-lane block addresses row 4g + m16/4, columns 16ct + 4(m16%4)..+3 and
+  // receives V[4g..4g+3][16ct + m16]: the A operand of O^T += V^T P^T for the keys its P holds.
+  const int vrow = 4 * g + (m16 >> 2);
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) {
+    const int off = v_off(vrow, 2 * ct + ((m16 & 3) >> 1)) + ((m16 & 1) << 3);
+    const s16x4 lo = lds_ld_tr16(Vl + off);
+    const s16x4 hi = lds_ld_tr16(Vl + off + 16 * ROWB);
+    union { s16x4 h[2]; bf16x8 v; } vt;
+    vt.h[0] = lo; vt.h[1] = hi;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      st.O[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pb[nt], st.O[nt][ct], 0, 0, 0);
+  }
+}
+
+// Normalise and store one partial: rows [rowbase, rowbase + 16 NT) of a unit with `nrows` rows.
+template <int NT>
+__device__ __forceinline__ void write_partial(const WaveState<NT>& st, float* po, float* pl, int slot, int nrows,
+                                              int rowbase, int lane) {
+  const int m16 = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    float l = st.l[nt], lr = st.lr[nt];
+    l += __shfl_xor(l, 16, 64);   l += __shfl_xor(l, 32, 64);
+    lr += __shfl_xor(lr, 16, 64); lr += __shfl_xor(lr, 32, 64);
+    const int row = rowbase + 16 * nt + m16;
+    if (row < nrows) {
+      const float inv = 1.f / lr;
+      float* o = po + ((size_t)slot * nrows + row) * D + 4 * g;
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+        const f32x4 v = st.O[nt][ct] * inv;
+        *reinterpret_cast<float4*>(o + 16 * ct) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+      if (g == 0) pl[(size_t)slot * nrows + row] = (st.m[nt] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f;
+    }
+  }
+}
+
+__device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+// ---- prefix run: tiles [t0, t0 + ntiles) of unit (p, j); the whole workgroup cooperates
+template <int NT>
+__device__ __forceinline__ void prefix_run(const SharedParams& P, char* lds, int p, int j, int t0, int ntiles, int Lp,
+                                           int slot, int tid) {
+  const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const char* kb = P.kp + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
+  const char* vb = P.vp + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
+  const int rowbase = 16 * NT * wv;
+  const bool active = rowbase < P.R;
+
+  bf16x8 qf[NT][4];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int row = rowbase + 16 * nt + m16;               // row = sample * r + head-in-group
+    const bool ok = row < P.R;
+    const int b = p * P.G + (ok ? row / P.r : 0), h = j * P.r + (ok ? row % P.r : 0);
+    const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+      qf[nt][ks] = *reinterpret_cast<bf16x8*>(&v);
+    }
+  }
+  WaveState<NT> st;
+  init_state(st);
+
+  const int lrow = tid >> 4, chunk = tid & 15;             // this thread stages rows lrow and 16 + lrow
+  u32x4 rk[2], rv[2];
+  auto issue = [&](int tile) {
+    const int key0 = (t0 + tile) * TK;
+    const int last = min(TK, Lp - key0) - 1;               // rows past the length re-read the last real row
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const size_t off = (size_t)(key0 + min(16 * i + lrow, last)) * ROWB + 16 * chunk;
+      rk[i] = ldg16(kb + off);
+      rv[i] = ldg16(vb + off);
+    }
+  };
+  issue(0);
+  for (int tt = 0; tt < ntiles; ++tt) {
+    char* stg = lds + (tt & 1) * STAGE_B;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      lds_st128(stg + k_off(16 * i + lrow, chunk), rk[i]);
+      lds_st128(stg + TILE_B + v_off(16 * i + lrow, chunk), rv[i]);
+    }
+    if (tt + 1 < ntiles) issue(tt + 1);
+    __syncthreads();
+    if (active) compute_tile<NT>(stg, stg + TILE_B, min(TK, Lp - (t0 + tt) * TK), qf, st, P.c, lane);
+  }
+  __syncthreads();                                          // the next run restarts at stage 0
+  if (active) write_partial<NT>(st, P.po, P.pl, slot, P.R, rowbase, lane);
+}
+
+// ---- suffix run: tiles [t0, t0 + ntiles) of unit (b, j); one wavefront, private 16 KB of LDS
+__device__ __forceinline__ void suffix_run(const SharedParams& P, char* wlds, int b, int j, int t0, int ntiles, int Ls,
+                                           int slot, int lane) {
+  const int m16 = lane & 15, g = lane >> 4;
+  const char* kb = P.ks + (size_t)(b * P.Hkv + j) * P.Ls_cap * ROWB;
+  const char* vb = P.vs + (size_t)(b * P.Hkv + j) * P.Ls_cap * ROWB;
+
+  bf16x8 qf[1][4];
+  {
+    const bool ok = m16 < P.r;
+    const char* qp = P.q + ((size_t)b * P.Hq + j * P.r + (ok ? m16 : 0)) * ROWB + 16 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+      qf[0][ks] = *reinterpret_cast<bf16x8*>(&v);
+    }
+  }
+  WaveState<1> st;
+  init_state(st);
+
+  const int lrow = lane >> 4, chunk = lane & 15;            // instruction i stages rows 4i + lrow: 1 KB contiguous
+  u32x4 rk[8], rv[8];
+  auto issue = [&](int tile) {
+    const int key0 = (t0 + tile) * TK;
+    const int last = min(TK, Ls - key0) - 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+      rk[i] = ldg16(kb + off);
+      rv[i] = ldg16(vb + off);
+    }
+  };
+  issue(0);
+  for (int tt = 0; tt < ntiles; ++tt) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      lds_st128(wlds + k_off(4 * i + lrow, chunk), rk[i]);
+      lds_st128(wlds + TILE_B + v_off(4 * i + lrow, chunk), rv[i]);
+    }
+    if (tt + 1 < ntiles) issue(tt + 1);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    compute_tile<1>(wlds, wlds + TILE_B, min(TK, Ls - (t0 + tt) * TK), qf, st, P.c, lane);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  }
+  write_partial<1>(st, P.so, P.sl, slot, P.r, 0, lane);
+}
+
+template <int NTP>
+__global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ int wsum[WG_WAVES];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
+
+  // ---- tile counts of all prompts and sequences, exclusive scan in LDS
+  int* X = reinterpret_cast<int*>(lds);
+  const int n = P.P + P.B + 1;
+  for (int i = tid; i < n; i += NTHREADS) {
+    int e = 0;
+    if (i < P.P) e = ceil_div(clampi(P.plens[i], 0, P.Lp_cap), TK);
+    else if (i < P.P + P.B) e = ceil_div(clampi(P.slens[i - P.P], 0, P.Ls_cap), TK);
+    X[i] = e;
+  }
+  __syncthreads();
+  {
+    const int per = ceil_div(n, NTHREADS);
+    const int c0 = min(tid * per, n), c1 = min(c0 + per, n);
+    int sum = 0;
+    for (int i = c0; i < c1; ++i) sum += X[i];
+    int incl = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += t;
+    }
+    if (lane == 63) wsum[wv] = incl;
+    __syncthreads();
+    int off = incl - sum;
+    for (int k = 0; k < wv; ++k) off += wsum[k];
+    for (int i = c0; i < c1; ++i) { const int e = X[i]; X[i] = off; off += e; }
+  }
+  __syncthreads();
+  const int cumP = X[P.P];
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.n_wg);
+  if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
+
+  // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
+  int ilo, ihi, klo, khi, ka, kb;
+  wg_prefix_range(sc, w, ilo, ihi);
+  wg_suffix_range(sc, w, klo, khi);
+  wave_suffix_range(klo, khi, wv, ka, kb);
+  int pp = 0, pj = 0, pt = 0, sb = 0, sj = 0, st0 = 0;
+  if (ilo < ihi) locate(X, P.P, P.Hkv, ilo, pp, pj, pt);
+  if (ka < kb) {
+    locate(X + P.P, P.B, P.Hkv, ka + cumP * P.Hkv, sb, sj, st0);   // X + P continues the prompt scan: shift the line
+  }
+  pp = uni(pp); pj = uni(pj); pt = uni(pt); sb = uni(sb); sj = uni(sj); st0 = uni(st0);
+  __syncthreads();                                          // the scan is dead; LDS becomes tile storage
+
+  // ---- prefix tiles of this workgroup (prefix_run ends with a barrier)
+  for_each_run(ilo, ihi, P.P, P.Hkv, pp, pj, pt,
+               [&](int p) { return ceil_div(clampi(P.plens[p], 0, P.Lp_cap), TK); },
+               [&](int p, int j, int t0, int run) {
+                 prefix_run<NTP>(P, lds, p, j, t0, run, clampi(P.plens[p], 0, P.Lp_cap), p * P.Hkv + j + w, tid);
+               });
+
+  // ---- suffix tiles of this wavefront, in its own quarter of the LDS
+  char* wlds = lds + wv * STAGE_B;
+  for_each_run(ka, kb, P.B, P.Hkv, sb, sj, st0,
+               [&](int b) { return ceil_div(clampi(P.slens[b], 0, P.Ls_cap), TK); },
+               [&](int b, int j, int t0, int run) {
+                 suffix_run(P, wlds, b, j, t0, run, clampi(P.slens[b], 0, P.Ls_cap),
+                            b * P.Hkv + j + WG_WAVES * w + wv, lane);
+               });
+}
+
+// ---- combine: 32 threads per (sequence, head) row, 4 columns each
+__global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
+  const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
+  const int c4 = (threadIdx.x & 31) * 4;
+  if (row >= P.B * P.Hq) return;
+  const int b = row / P.Hq, h = row % P.Hq;
+  const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
+  const int* X = P.cum;
+  const int cumP = X[P.P];
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.n_wg);
+
+  float M = -INFINITY, z = 0.f;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto add = [&](const float* o, float l) {                 // online merge; parts arrive in slot order
+    const float Mn = fmaxf(M, l);
+    const float a = __expf(M - Mn), wgt = __expf(l - Mn);
+    const float4 v = *reinterpret_cast<const float4*>(o);
+    z = z * a + wgt;
+    acc.x = acc.x * a + wgt * v.x; acc.y = acc.y * a + wgt * v.y;
+    acc.z = acc.z * a + wgt * v.z; acc.w = acc.w * a + wgt * v.w;
+    M = Mn;
+  };
+  const int prow = gs * P.r + hi_;                          // row inside the prefix unit: sample-major
+  for_each_prefix_part(sc, X, P.Hkv, p, j, [&](int w) {
+    const size_t idx = (size_t)(p * P.Hkv + j + w) * P.R + prow;
+    add(P.po + idx * D + c4, P.pl[idx]);
+  });
+  for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int w, int v) {
+    const size_t idx = (size_t)(b * P.Hkv + j + WG_WAVES * w + v) * P.r + hi_;
+    add(P.so + idx * D + c4, P.sl[idx]);
+  });
+  const float inv = z > 0.f ? 1.f / z : 0.f;
+  *reinterpret_cast<float4*>(P.out + (size_t)row * D + c4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  if (P.lse && c4 == 0) P.lse[row] = z > 0.f ? M + __logf(z) : -INFINITY;
+}
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Layout { size_t cum, pl, po, sl, so, total; };
+
+Layout layout(const rlda_desc& ds) {
+  const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, R = r * ds.G;
+  const size_t nps = (size_t)ds.P * ds.Hkv + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
+  Layout L;
+  size_t o = 0;
+  L.cum = o; o = align256(o + (ds.P + B + 1) * 4);
+  L.pl = o;  o = align256(o + nps * R * 4);
+  L.po = o;  o = align256(o + nps * R * D * 4);
+  L.sl = o;  o = align256(o + nss * r * 4);
+  L.so = o;  o = align256(o + nss * r * D * 4);
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+bool shared_supported(const rlda_desc& ds) {
+  if (ds.dtype != RLDA_BF16 || ds.d != D) return false;
+  const int64_t B = (int64_t)ds.P * ds.G;
+  const int r = ds.Hq / ds.Hkv;
+  if (r > 16 || (int64_t)r * ds.G > 128) return false;                  // rows of one KV group: <= 8 MFMA row blocks
+  if (ds.P + B + 1 > MAX_SCAN) return false;                            // the length scan lives in LDS
+  const int64_t tiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) * PREFIX_WEIGHT +
+                        B * ds.Hkv * ceil_div(ds.Ls_cap, TK);
+  if (tiles + N_WG >= (int64_t)1 << 30) return false;                   // 32-bit tile arithmetic
+  if ((int64_t)ds.Lp_cap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
+  return true;
+}
+
+size_t shared_workspace_bytes(const rlda_desc& ds) { return layout(ds).total; }
+
+hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
+  const Layout L = layout(ds);
+  char* ws = static_cast<char*>(ds.workspace);
+  SharedParams P;
+  P.q = static_cast<const char*>(ds.q);
+  P.kp = static_cast<const char*>(ds.k_prefix); P.vp = static_cast<const char*>(ds.v_prefix);
+  P.ks = static_cast<const char*>(ds.k_suffix); P.vs = static_cast<const char*>(ds.v_suffix);
+  P.plens = ds.prefix_lens; P.slens = ds.suffix_lens;
+  P.out = ds.out; P.lse = ds.lse;
+  P.cum = reinterpret_cast<int32_t*>(ws + L.cum);
+  P.pl = reinterpret_cast<float*>(ws + L.pl); P.po = reinterpret_cast<float*>(ws + L.po);
+  P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<float*>(ws + L.so);
+  P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
+  P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
+  P.wP = PREFIX_WEIGHT; P.n_wg = N_WG;
+  P.c = ds.scale * 1.4426950408889634f;
+
+  static bool attr_set = false;                             // 64 KB of dynamic LDS needs an opt-in
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&partial_kernel<1>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&partial_kernel<2>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  if (P.R <= 64) hipLaunchKernelGGL((partial_kernel<1>), dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
+  else           hipLaunchKernelGGL((partial_kernel<2>), dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rows = P.B * P.Hq;
+  hipLaunchKernelGGL(combine_kernel, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  return hipGetLastError();
+}
+
 }  // namespace rlda

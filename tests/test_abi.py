@@ -102,3 +102,16 @@ def test_lse_combine_argument_checks():
     assert f(None, None, -1, 4, 128, None, None, None) == B.RLDA_ERR_INVALID
     assert f(None, None, 2, 4, 128, 0x1000, None, None) == B.RLDA_ERR_INVALID
     assert f(None, None, 2, 0, 128, None, None, None) == B.RLDA_OK
+
+
+def test_auto_selects_the_shared_prefix_path_for_bf16_d128():
+    for w in ("vlm3b", "vlm7b", "agentic", "highbatch"):
+        from paper_2512_21450_amd import workloads as wl
+        W = wl.WORKLOADS[w]
+        ds = B.make_desc(B.RLDA_BF16, W.P, W.G, W.Hq, W.Hkv, W.d, W.Lp_cap, W.Ls_cap, W.scale)
+        assert B.rl_decode_attn_plan(ds) == B.RLDA_ALGO_SHARED
+        assert B.rl_decode_attn_workspace_bytes(ds) > 0
+    # shapes outside the MFMA path fall back to the simple kernel under AUTO
+    assert B.rl_decode_attn_plan(good(d=64)) == B.RLDA_ALGO_SIMPLE
+    assert B.rl_decode_attn_plan(good(Hq=64, Hkv=2)) == B.RLDA_ALGO_SIMPLE          # 32 heads per KV head
+    assert B.rl_decode_attn_plan(good(Hq=64, Hkv=2, algo=B.RLDA_ALGO_SHARED)) == B.RLDA_ERR_UNSUPPORTED

@@ -1,0 +1,97 @@
+"""The static work partition of the shared-prefix path, checked on the host:
+every tile is processed exactly once, partial slots are unique, and the
+combine step reads exactly the partials the walk produces, in line order."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from paper_2512_21450_amd import binding as B
+from paper_2512_21450_amd import workloads as wl
+
+TK = 32
+_f = B._lib.rl_decode_attn_debug_partition
+_f.restype = ctypes.c_int64
+_f.argtypes = [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2 + [ctypes.c_void_p, ctypes.c_int64,
+                                                               ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+
+
+def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
+    plens = np.ascontiguousarray(plens, np.int32)
+    slens = np.ascontiguousarray(slens, np.int32)
+    cap = 4 * (P * (G + 1) * Hkv + 8 * 512) + 16
+    runs = np.zeros((cap, 8), np.int32)
+    parts = np.zeros((cap, 6), np.int32)
+    npart = ctypes.c_int64(0)
+    nr = _f(P, G, Hkv, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
+            parts.ctypes.data, cap, ctypes.byref(npart))
+    assert 0 <= nr <= cap and npart.value <= cap
+    return runs[:nr], parts[:npart.value]
+
+
+def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
+    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens)
+    tp = -(-np.clip(plens, 0, Lp_cap) // TK)
+    ts = -(-np.clip(slens, 0, Ls_cap) // TK)
+    # coverage: each unit's tiles [0, T) are tiled by its runs without gap or overlap
+    for kind, counts in ((0, tp), (1, ts)):
+        rk = runs[runs[:, 0] == kind]
+        seen = {}
+        for _, major, j, t0, n, w, v, slot in rk:
+            assert n > 0
+            seen.setdefault((major, j), []).append((t0, n))
+        for major, T in enumerate(counts):
+            for j in range(Hkv):
+                segs = sorted(seen.pop((major, j), []))
+                pos = 0
+                for t0, n in segs:
+                    assert t0 == pos, (kind, major, j, segs)
+                    pos += n
+                assert pos == T, (kind, major, j, segs, T)
+        assert not seen
+    # slots: unique per kind, inside the workspace the library sizes
+    for kind, nslots in ((0, P * Hkv + 512), (1, P * G * Hkv + 4 * 512)):
+        sl = runs[runs[:, 0] == kind][:, 7]
+        assert len(set(sl.tolist())) == len(sl)
+        assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
+    # the combine enumeration == the set of runs, and per unit in increasing line order
+    key_r = sorted((int(k), int(m), int(j), int(w), int(v), int(s)) for k, m, j, _, _, w, v, s in runs)
+    key_p = sorted(tuple(int(x) for x in row) for row in parts)
+    assert key_r == key_p
+    # balance: no workgroup holds more than its share + one tile
+    total = int(tp.sum() + ts.sum()) * Hkv
+    share = -(-total // 512) if total else 0
+    load = np.zeros(512, np.int64)
+    np.add.at(load, runs[:, 5], runs[:, 4])
+    assert load.max() <= share + 1
+    return runs
+
+
+@pytest.mark.parametrize("name", ["vlm3b", "vlm7b", "agentic", "highbatch"])
+def test_partition_of_the_benchmark_workloads(name):
+    w = wl.WORKLOADS[name]
+    rng = np.random.default_rng(w.seed)
+    pl = wl._draw_lens(rng, w.prefix, w.P, w.Lp_cap)
+    sl = wl._draw_lens(rng, w.suffix, w.B, w.Ls_cap)
+    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl)
+    assert len(runs) > 0
+
+
+def test_partition_edge_cases():
+    rng = np.random.default_rng(0)
+    # nothing at all, prefix only, suffix only, single tile, fewer tiles than workgroups
+    check(2, 3, 2, 64, 64, [0, 0], [0] * 6)
+    check(2, 3, 2, 64, 64, [64, 1], [0] * 6)
+    check(2, 3, 2, 64, 64, [0, 0], [5, 0, 64, 0, 0, 33])
+    check(1, 1, 1, 40, 40, [1], [0])
+    check(3, 2, 4, 100, 100, [100, 0, 31], [0, 100, 1, 32, 33, 0])
+    # zero-length prompts/sequences at the start, in the middle and at the end
+    check(5, 2, 2, 500, 500, [0, 300, 0, 0, 77], [0, 0, 400, 0, 12, 0, 0, 500, 0, 0])
+    # lengths outside [0, cap] clamp
+    check(2, 2, 2, 100, 50, [-5, 1000], [999, -1, 50, 3])
+    for _ in range(20):
+        P, G, Hkv = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        Lp_cap, Ls_cap = int(rng.integers(0, 3000)), int(rng.integers(0, 5000))
+        pl = rng.integers(0, Lp_cap + 1, P) * (rng.random(P) < 0.8)
+        sl = rng.integers(0, Ls_cap + 1, P * G) * (rng.random(P * G) < 0.7)
+        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl)
