@@ -5,7 +5,7 @@
 // head) and owns ceil(Lp/TK) tiles; a "suffix unit" is one (sequence, KV head)
 // and owns ceil(Ls/TK) tiles.  All tiles are laid on one line, prefix tiles
 // first (prompt-major, then KV head, then tile), then suffix tiles (sequence-
-// major, then KV head, then tile).  A prefix tile weighs wP, a suffix tile 1;
+// major, then KV head, then tile).  A prefix tile weighs wP, a suffix tile wS;
 // workgroup w takes the tiles whose weighted position falls in [w*S, (w+1)*S).
 // Its prefix tiles are processed by the whole workgroup (one shared K/V tile in
 // LDS, one 16-row query block per wavefront); its suffix tiles are cut into four
@@ -24,12 +24,14 @@ namespace rlda {
 constexpr int TK = 32;            // keys per tile
 constexpr int WG_WAVES = 4;       // wavefronts per workgroup
 constexpr int N_WG = 512;         // workgroups of the partial kernel: 256 CUs x 2 resident
-constexpr int PREFIX_WEIGHT = 1;  // weight of a prefix tile on the line (a suffix tile weighs 1)
+constexpr int PREFIX_WEIGHT = 4;  // weight of a prefix tile on the line
+constexpr int SUFFIX_WEIGHT = 4;  // weight of a suffix tile on the line
 
 struct Sched {
   int NPT;      // prefix tiles in total (all units)
   int NST;      // suffix tiles in total
   int wP;       // weight of a prefix tile
+  int wS;       // weight of a suffix tile
   int S;        // weighted share of one workgroup (>= 1)
   int n_wg;     // workgroups
 };
@@ -37,10 +39,10 @@ struct Sched {
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int n_wg) {
+__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_wg) {
   Sched s;
-  s.NPT = NPT; s.NST = NST; s.wP = wP; s.n_wg = n_wg;
-  const int W = wP * NPT + NST;
+  s.NPT = NPT; s.NST = NST; s.wP = wP; s.wS = wS; s.n_wg = n_wg;
+  const int W = wP * NPT + wS * NST;
   s.S = W > 0 ? ceil_div(W, n_wg) : 1;
   return s;
 }
@@ -55,10 +57,10 @@ __host__ __device__ inline int prefix_tile_owner(const Sched& s, int i) { return
 // suffix tiles [lo, hi) of workgroup w
 __host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
   const int base = s.wP * s.NPT;
-  lo = clampi(w * s.S - base, 0, s.NST);
-  hi = clampi((w + 1) * s.S - base, 0, s.NST);
+  lo = w * s.S <= base ? 0 : clampi(ceil_div(w * s.S - base, s.wS), 0, s.NST);
+  hi = (w + 1) * s.S <= base ? 0 : clampi(ceil_div((w + 1) * s.S - base, s.wS), 0, s.NST);
 }
-__host__ __device__ inline int suffix_tile_owner(const Sched& s, int k) { return (s.wP * s.NPT + k) / s.S; }
+__host__ __device__ inline int suffix_tile_owner(const Sched& s, int k) { return (s.wP * s.NPT + s.wS * k) / s.S; }
 
 // run of wavefront v inside the workgroup's suffix range
 __host__ __device__ inline void wave_suffix_range(int lo, int hi, int v, int& a, int& b) {
@@ -110,7 +112,11 @@ __host__ __device__ inline void for_each_prefix_part(const Sched& s, const int* 
   const int T = Xp[p + 1] - Xp[p];
   if (T <= 0) return;
   const int is = Xp[p] * Hkv + j * T, ie = is + T;
-  for (int w = prefix_tile_owner(s, is); w <= prefix_tile_owner(s, ie - 1); ++w) fn(w);
+  for (int w = prefix_tile_owner(s, is); w <= prefix_tile_owner(s, ie - 1); ++w) {
+    int lo, hi;                                  // with a share below one tile weight some workgroups own nothing
+    wg_prefix_range(s, w, lo, hi);
+    if ((lo > is ? lo : is) < (hi < ie ? hi : ie)) fn(w);
+  }
 }
 
 // (workgroup, wavefront) pairs holding a partial of suffix unit (b, j): fn(w, v) in line order.
@@ -125,6 +131,7 @@ __host__ __device__ inline void for_each_suffix_part(const Sched& s, const int* 
     int lo, hi;
     wg_suffix_range(s, w, lo, hi);
     const int k0 = ks > lo ? ks : lo, k1 = (ke < hi ? ke : hi) - 1;
+    if (k0 > k1) continue;
     for (int v = suffix_tile_wave(lo, hi, k0); v <= suffix_tile_wave(lo, hi, k1); ++v) fn(w, v);
   }
 }

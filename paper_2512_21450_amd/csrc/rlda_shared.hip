@@ -21,6 +21,7 @@
 // lane until the partial is written.
 #include "rlda_internal.h"
 #include "rlda_sched.h"
+#include <stdlib.h>
 
 namespace rlda {
 namespace {
@@ -49,7 +50,7 @@ struct SharedParams {
   float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
-  int wP, n_wg;
+  int wP, wS, n_wg;
   float c;                // scale * log2(e): scores are kept in base 2
 };
 
@@ -204,31 +205,41 @@ __device__ __forceinline__ void prefix_run(const SharedParams& P, char* lds, int
   WaveState<NT> st;
   init_state(st);
 
-  const int lrow = tid >> 4, chunk = tid & 15;             // this thread stages rows lrow and 16 + lrow
-  u32x4 rk[2], rv[2];
+  // Tiles are staged in groups of TPG, one LDS stage each.  A tile is fetched by WPT = 4 / TPG
+  // wavefronts (a whole tile per wavefront when NT == 1), so a workgroup keeps as many bytes in
+  // flight as four suffix wavefronts do; all four wavefronts then compute on every stage.
+  constexpr int TPG = NT == 1 ? 4 : 2, WPT = WG_WAVES / TPG, NLD = 8 / WPT;
+  const int my_tile = wv / WPT, row0 = (wv % WPT) * (TK / WPT) + (lane >> 4), chunk = lane & 15;
+  u32x4 rk[NLD], rv[NLD];
   auto issue = [&](int tile) {
     const int key0 = (t0 + tile) * TK;
     const int last = min(TK, Lp - key0) - 1;               // rows past the length re-read the last real row
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const size_t off = (size_t)(key0 + min(16 * i + lrow, last)) * ROWB + 16 * chunk;
+    for (int i = 0; i < NLD; ++i) {
+      const size_t off = (size_t)(key0 + min(row0 + 4 * i, last)) * ROWB + 16 * chunk;
       rk[i] = ldg16(kb + off);
       rv[i] = ldg16(vb + off);
     }
   };
-  issue(0);
-  for (int tt = 0; tt < ntiles; ++tt) {
-    char* stg = lds + (tt & 1) * STAGE_B;
+  if (my_tile < ntiles) issue(my_tile);
+  for (int g0 = 0; g0 < ntiles; g0 += TPG) {
+    if (g0 + my_tile < ntiles) {
+      char* stg = lds + my_tile * STAGE_B;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      lds_st128(stg + k_off(16 * i + lrow, chunk), rk[i]);
-      lds_st128(stg + TILE_B + v_off(16 * i + lrow, chunk), rv[i]);
+      for (int i = 0; i < NLD; ++i) {
+        lds_st128(stg + k_off(row0 + 4 * i, chunk), rk[i]);
+        lds_st128(stg + TILE_B + v_off(row0 + 4 * i, chunk), rv[i]);
+      }
     }
-    if (tt + 1 < ntiles) issue(tt + 1);
+    if (g0 + TPG + my_tile < ntiles) issue(g0 + TPG + my_tile);
     __syncthreads();
-    if (active) compute_tile<NT>(stg, stg + TILE_B, min(TK, Lp - (t0 + tt) * TK), qf, st, P.c, lane);
+    if (active) {
+      for (int s = 0; s < TPG && g0 + s < ntiles; ++s)
+        compute_tile<NT>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, Lp - (t0 + g0 + s) * TK), qf, st,
+                         P.c, lane);
+    }
+    __syncthreads();                                        // stages are rewritten by the next group / next run
   }
-  __syncthreads();                                          // the next run restarts at stage 0
   if (active) write_partial<NT>(st, P.po, P.pl, slot, P.R, rowbase, lane);
 }
 
@@ -316,7 +327,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.n_wg);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_wg);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -358,7 +369,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.n_wg);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_wg);
 
   float M = -INFINITY, z = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -412,7 +423,7 @@ bool shared_supported(const rlda_desc& ds) {
   if (r > 16 || (int64_t)r * ds.G > 128) return false;                  // rows of one KV group: <= 8 MFMA row blocks
   if (ds.P + B + 1 > MAX_SCAN) return false;                            // the length scan lives in LDS
   const int64_t tiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) * PREFIX_WEIGHT +
-                        B * ds.Hkv * ceil_div(ds.Ls_cap, TK);
+                        B * ds.Hkv * ceil_div(ds.Ls_cap, TK) * SUFFIX_WEIGHT;
   if (tiles + N_WG >= (int64_t)1 << 30) return false;                   // 32-bit tile arithmetic
   if ((int64_t)ds.Lp_cap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
   return true;
@@ -434,7 +445,10 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
   P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<float*>(ws + L.so);
   P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
-  P.wP = PREFIX_WEIGHT; P.n_wg = N_WG;
+  P.wP = PREFIX_WEIGHT; P.wS = SUFFIX_WEIGHT; P.n_wg = N_WG;
+  if (const char* e = getenv("RLDA_WP")) P.wP = atoi(e);      // TEMP experiment
+  if (const char* e = getenv("RLDA_WS")) P.wS = atoi(e);      // TEMP experiment
+  if (const char* e = getenv("RLDA_NWG")) P.n_wg = atoi(e);   // TEMP experiment (<= N_WG)
   P.c = ds.scale * 1.4426950408889634f;
 
   static bool attr_set = false;                             // 64 KB of dynamic LDS needs an opt-in
@@ -447,7 +461,7 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  if (P.R <= 64) hipLaunchKernelGGL((partial_kernel<1>), dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
+  if (P.R <= 64) hipLaunchKernelGGL((partial_kernel<1>), dim3(P.n_wg), dim3(NTHREADS), LDS_BYTES, stream, P);
   else           hipLaunchKernelGGL((partial_kernel<2>), dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
