@@ -110,7 +110,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
   for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
   for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
   const int cumP = X[P];
-  const Sched sc = make_sched(cumP * Hkv, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_WG);
+  const Sched sc = make_sched(cumP * Hkv, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   int64_t nr = 0, np = 0;
   auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
     if (runs && nr < runs_cap) {
@@ -136,7 +136,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
       int b, j, t;
       locate(X.data() + P, B, Hkv, ka + cumP * Hkv, b, j, t);
       for_each_run(ka, kb, B, Hkv, b, j, t, ts, [&](int bb, int jj, int t0, int n) {
-        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * w + v);
+        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * suffix_wg_rank(sc, w) + v);
       });
     }
   }
@@ -152,8 +152,9 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
       for_each_prefix_part(sc, X.data(), Hkv, p, j, [&](int w) { put_part(0, p, j, w, -1, p * Hkv + j + w); });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)
-      for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j,
-                           [&](int w, int v) { put_part(1, b, j, w, v, b * Hkv + j + WG_WAVES * w + v); });
+      for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j, [&](int rank, int v) {
+        put_part(1, b, j, rank % 2 ? N_CU + rank / 2 : rank / 2, v, b * Hkv + j + WG_WAVES * rank + v);
+      });
   *n_parts = np;
   return nr;
 }

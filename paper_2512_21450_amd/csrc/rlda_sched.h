@@ -3,18 +3,27 @@
 //
 // Keys are processed in tiles of TK rows.  A "prefix unit" is one (prompt, KV
 // head) and owns ceil(Lp/TK) tiles; a "suffix unit" is one (sequence, KV head)
-// and owns ceil(Ls/TK) tiles.  All tiles are laid on one line, prefix tiles
-// first (prompt-major, then KV head, then tile), then suffix tiles (sequence-
-// major, then KV head, then tile).  A prefix tile weighs wP, a suffix tile wS;
-// workgroup w takes the tiles whose weighted position falls in [w*S, (w+1)*S).
-// Its prefix tiles are processed by the whole workgroup (one shared K/V tile in
-// LDS, one 16-row query block per wavefront); its suffix tiles are cut into four
-// consecutive runs, one per wavefront.  Every maximal run of tiles of one unit
-// inside one workgroup (prefix) or one wavefront (suffix) yields one partial
-// (o, lse); its slot is unit + workgroup (prefix) or unit + 4*workgroup +
-// wavefront (suffix), which is unique because both terms are monotone along
-// the line.  Nothing here depends on run-time timing, so the split and hence
-// the rounding order is the same on every call.
+// and owns ceil(Ls/TK) tiles.  Prefix tiles form one line (prompt-major, then KV
+// head, then tile), suffix tiles another (sequence-major, then KV head, then tile).
+//
+// The partial kernel runs 2 * N_CU workgroups, two per compute unit: workgroup
+// c ("A") and workgroup N_CU + c ("B") form pair c.  Every pair gets the same
+// share of each line (position N*c/N_CU .. N*(c+1)/N_CU), so that every compute
+// unit carries the same mix of work and all finish together.  A takes the pair's
+// prefix tiles, which the whole workgroup processes together (one shared K/V
+// tile in LDS, 16-row query blocks spread over the wavefronts), plus the first
+// xA of the pair's suffix tiles; B takes the rest of the suffix tiles.  xA
+// evens out the two by tile weight (a prefix tile costs wP, a suffix tile wS:
+// prefix tiles carry several times the matrix work per byte).  A workgroup's
+// suffix tiles are cut into WG_WAVES consecutive runs, one per wavefront.
+// While A works through prefix tiles, which are bound by matrix and LDS work, B
+// streams suffix tiles, which are bound by memory, on the same compute unit.
+//
+// Every maximal run of tiles of one unit inside one workgroup (prefix) or one
+// wavefront (suffix) yields one partial (o, lse); its slot is unit + c (prefix)
+// or unit + WG_WAVES*(2c + [B]) + wavefront (suffix), unique because both terms
+// are monotone along the line.  Nothing here depends on run-time timing, so
+// the split and hence the rounding order is the same on every call.
 #pragma once
 
 #include <stdint.h>
@@ -23,44 +32,55 @@ namespace rlda {
 
 constexpr int TK = 32;            // keys per tile
 constexpr int WG_WAVES = 4;       // wavefronts per workgroup
-constexpr int N_WG = 512;         // workgroups of the partial kernel: 256 CUs x 2 resident
-constexpr int PREFIX_WEIGHT = 4;  // weight of a prefix tile on the line
-constexpr int SUFFIX_WEIGHT = 4;  // weight of a suffix tile on the line
+constexpr int N_CU = 256;         // workgroup pairs: one per compute unit
+constexpr int N_WG = 2 * N_CU;    // workgroups of the partial kernel
+constexpr int PREFIX_WEIGHT = 6;  // cost of a prefix tile ...
+constexpr int SUFFIX_WEIGHT = 4;  // ... relative to a suffix tile
 
 struct Sched {
   int NPT;      // prefix tiles in total (all units)
   int NST;      // suffix tiles in total
-  int wP;       // weight of a prefix tile
-  int wS;       // weight of a suffix tile
-  int S;        // weighted share of one workgroup (>= 1)
-  int n_wg;     // workgroups
+  int wP, wS;   // tile weights
+  int n_cu;     // workgroup pairs
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_wg) {
+__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {
   Sched s;
-  s.NPT = NPT; s.NST = NST; s.wP = wP; s.wS = wS; s.n_wg = n_wg;
-  const int W = wP * NPT + wS * NST;
-  s.S = W > 0 ? ceil_div(W, n_wg) : 1;
+  s.NPT = NPT; s.NST = NST; s.wP = wP; s.wS = wS; s.n_cu = n_cu;
   return s;
 }
 
-// prefix tiles [lo, hi) of workgroup w: tile i belongs to workgroup floor(wP*i / S)
-__host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
-  lo = clampi(ceil_div(w * s.S, s.wP), 0, s.NPT);
-  hi = clampi(ceil_div((w + 1) * s.S, s.wP), 0, s.NPT);
+// pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles
+__host__ __device__ inline int share(int N, int c, int n_cu) { return (int)(((long long)N * c) / n_cu); }
+// the pair that owns position i: the largest c with share(N, c) <= i
+__host__ __device__ inline int share_owner(int N, int i, int n_cu) {
+  return (int)((((long long)(i + 1) * n_cu) + N - 1) / N) - 1;
 }
-__host__ __device__ inline int prefix_tile_owner(const Sched& s, int i) { return (s.wP * i) / s.S; }
 
-// suffix tiles [lo, hi) of workgroup w
-__host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
-  const int base = s.wP * s.NPT;
-  lo = w * s.S <= base ? 0 : clampi(ceil_div(w * s.S - base, s.wS), 0, s.NST);
-  hi = (w + 1) * s.S <= base ? 0 : clampi(ceil_div((w + 1) * s.S - base, s.wS), 0, s.NST);
+// prefix tiles [lo, hi) of workgroup w (B workgroups have none)
+__host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
+  if (w >= s.n_cu) { lo = hi = 0; return; }
+  lo = share(s.NPT, w, s.n_cu);
+  hi = share(s.NPT, w + 1, s.n_cu);
 }
-__host__ __device__ inline int suffix_tile_owner(const Sched& s, int k) { return (s.wP * s.NPT + s.wS * k) / s.S; }
+__host__ __device__ inline int prefix_tile_owner(const Sched& s, int i) { return share_owner(s.NPT, i, s.n_cu); }
+
+// suffix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi)
+__host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
+  lo = share(s.NST, c, s.n_cu);
+  hi = share(s.NST, c + 1, s.n_cu);
+  const int np = share(s.NPT, c + 1, s.n_cu) - share(s.NPT, c, s.n_cu);
+  mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
+}
+__host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
+  int a, m, b;
+  pair_suffix_range(s, w % s.n_cu, a, m, b);
+  if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
+}
+__host__ __device__ inline int suffix_tile_pair(const Sched& s, int k) { return share_owner(s.NST, k, s.n_cu); }
 
 // run of wavefront v inside the workgroup's suffix range
 __host__ __device__ inline void wave_suffix_range(int lo, int hi, int v, int& a, int& b) {
@@ -72,6 +92,8 @@ __host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {
   const int q = ceil_div(hi - lo, WG_WAVES);
   return (k - lo) / q;
 }
+// slot term of workgroup w on the suffix line (A and B of a pair are neighbours there)
+__host__ __device__ inline int suffix_wg_rank(const Sched& s, int w) { return w < s.n_cu ? 2 * w : 2 * (w - s.n_cu) + 1; }
 
 // ---- walking the line -------------------------------------------------------------------
 // X is the exclusive scan of per-head tile counts over `n` prompts (or sequences); every
@@ -106,33 +128,36 @@ __host__ __device__ inline void for_each_run(int lo, int hi, int n, int Hkv, int
   }
 }
 
-// Workgroups holding a partial of prefix unit (p, j): fn(w) in increasing w.  Xp = scan over prompts.
+// Workgroups holding a partial of prefix unit (p, j): fn(c) in increasing c.  Xp = scan over prompts.
 template <class Fn>
 __host__ __device__ inline void for_each_prefix_part(const Sched& s, const int* Xp, int Hkv, int p, int j, Fn fn) {
   const int T = Xp[p + 1] - Xp[p];
   if (T <= 0) return;
   const int is = Xp[p] * Hkv + j * T, ie = is + T;
-  for (int w = prefix_tile_owner(s, is); w <= prefix_tile_owner(s, ie - 1); ++w) {
-    int lo, hi;                                  // with a share below one tile weight some workgroups own nothing
-    wg_prefix_range(s, w, lo, hi);
-    if ((lo > is ? lo : is) < (hi < ie ? hi : ie)) fn(w);
+  for (int c = prefix_tile_owner(s, is); c <= prefix_tile_owner(s, ie - 1); ++c) {
+    int lo, hi;                                  // with fewer tiles than pairs some own nothing
+    wg_prefix_range(s, c, lo, hi);
+    if ((lo > is ? lo : is) < (hi < ie ? hi : ie)) fn(c);
   }
 }
 
-// (workgroup, wavefront) pairs holding a partial of suffix unit (b, j): fn(w, v) in line order.
-// Xs = scan over sequences, xs0 = its value at sequence 0 (subtracted, so Xs may continue Xp).
+// (suffix rank of the workgroup, wavefront) pairs holding a partial of suffix unit (b, j): fn(rank, v)
+// in line order.  Xs = scan over sequences, xs0 = its value at sequence 0 (so Xs may continue Xp).
 template <class Fn>
 __host__ __device__ inline void for_each_suffix_part(const Sched& s, const int* Xs, int xs0, int Hkv, int b, int j,
                                                      Fn fn) {
   const int T = Xs[b + 1] - Xs[b];
   if (T <= 0) return;
   const int ks = (Xs[b] - xs0) * Hkv + j * T, ke = ks + T;
-  for (int w = suffix_tile_owner(s, ks); w <= suffix_tile_owner(s, ke - 1); ++w) {
-    int lo, hi;
-    wg_suffix_range(s, w, lo, hi);
-    const int k0 = ks > lo ? ks : lo, k1 = (ke < hi ? ke : hi) - 1;
-    if (k0 > k1) continue;
-    for (int v = suffix_tile_wave(lo, hi, k0); v <= suffix_tile_wave(lo, hi, k1); ++v) fn(w, v);
+  for (int c = suffix_tile_pair(s, ks); c <= suffix_tile_pair(s, ke - 1); ++c) {
+    int lo, mid, hi;
+    pair_suffix_range(s, c, lo, mid, hi);
+    for (int half = 0; half < 2; ++half) {
+      const int a = half ? mid : lo, e = half ? hi : mid;
+      const int k0 = ks > a ? ks : a, k1 = (ke < e ? ke : e) - 1;
+      if (k0 > k1) continue;
+      for (int v = suffix_tile_wave(a, e, k0); v <= suffix_tile_wave(a, e, k1); ++v) fn(2 * c + half, v);
+    }
   }
 }
 

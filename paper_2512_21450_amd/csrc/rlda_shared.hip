@@ -31,7 +31,7 @@ constexpr int ROWB = D * 2;                       // bytes per K/V row
 constexpr int TILE_B = TK * ROWB;                 // 8 KB: one K or V tile
 constexpr int STAGE_B = 2 * TILE_B;               // K tile + V tile
 constexpr int NTHREADS = 64 * WG_WAVES;
-constexpr int LDS_BYTES = WG_WAVES * STAGE_B;     // 64 KB -> two workgroups per CU
+constexpr int LDS_BYTES = WG_WAVES * STAGE_B;     // 64 KB: one stage per wavefront, two workgroups per CU
 constexpr int MAX_SCAN = LDS_BYTES / 4;           // ints of LDS available to the length scan
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -50,7 +50,7 @@ struct SharedParams {
   float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
-  int wP, wS, n_wg;
+  int wP, wS, n_cu;
   float c;                // scale * log2(e): scores are kept in base 2
 };
 
@@ -76,6 +76,20 @@ __device__ __forceinline__ void lds_st128(char* p, u32x4 v) { *RLDA_LDS(u32x4, p
 __device__ __forceinline__ s16x4 lds_ld_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(RLDA_LDS(s16x4, const_cast<char*>(p)));
 }
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also drains the vector-memory
+// counter, which would force the global loads just issued for the next tiles to land first.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Explicit "all vector-memory loads have landed".  Placed right before a tile's registers are
+// copied to LDS (where that wait is due anyway), it also tells the compiler that the query
+// fragments loaded earlier are resident, so that it does not drain the loads issued for the next
+// tile when the fragments are first used inside the loop.
+__device__ __forceinline__ void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 template <int NT>
 __device__ __forceinline__ void init_state(WaveState<NT>& st) {
@@ -179,120 +193,239 @@ __device__ __forceinline__ void write_partial(const WaveState<NT>& st, float* po
 
 __device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
 
-// ---- prefix run: tiles [t0, t0 + ntiles) of unit (p, j); the whole workgroup cooperates
-template <int NT>
-__device__ __forceinline__ void prefix_run(const SharedParams& P, char* lds, int p, int j, int t0, int ntiles, int Lp,
-                                           int slot, int tid) {
-  const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  const char* kb = P.kp + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
-  const char* vb = P.vp + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
-  const int rowbase = 16 * NT * wv;
-  const bool active = rowbase < P.R;
+// ---- a position on the work line: unit (u, j), tile t inside it, and the unit's size
+struct Cur { int u, j, t, T, L; };                          // T tiles, L keys
 
-  bf16x8 qf[NT][4];
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    const int row = rowbase + 16 * nt + m16;               // row = sample * r + head-in-group
-    const bool ok = row < P.R;
-    const int b = p * P.G + (ok ? row / P.r : 0), h = j * P.r + (ok ? row % P.r : 0);
-    const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
-      qf[nt][ks] = *reinterpret_cast<bf16x8*>(&v);
-    }
-  }
-  WaveState<NT> st;
-  init_state(st);
-
-  // Tiles are staged in groups of TPG, one LDS stage each.  A tile is fetched by WPT = 4 / TPG
-  // wavefronts (a whole tile per wavefront when NT == 1), so a workgroup keeps as many bytes in
-  // flight as four suffix wavefronts do; all four wavefronts then compute on every stage.
-  constexpr int TPG = NT == 1 ? 4 : 2, WPT = WG_WAVES / TPG, NLD = 8 / WPT;
-  const int my_tile = wv / WPT, row0 = (wv % WPT) * (TK / WPT) + (lane >> 4), chunk = lane & 15;
-  u32x4 rk[NLD], rv[NLD];
-  auto issue = [&](int tile) {
-    const int key0 = (t0 + tile) * TK;
-    const int last = min(TK, Lp - key0) - 1;               // rows past the length re-read the last real row
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const size_t off = (size_t)(key0 + min(row0 + 4 * i, last)) * ROWB + 16 * chunk;
-      rk[i] = ldg16(kb + off);
-      rv[i] = ldg16(vb + off);
-    }
-  };
-  if (my_tile < ntiles) issue(my_tile);
-  for (int g0 = 0; g0 < ntiles; g0 += TPG) {
-    if (g0 + my_tile < ntiles) {
-      char* stg = lds + my_tile * STAGE_B;
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        lds_st128(stg + k_off(row0 + 4 * i, chunk), rk[i]);
-        lds_st128(stg + TILE_B + v_off(row0 + 4 * i, chunk), rv[i]);
-      }
-    }
-    if (g0 + TPG + my_tile < ntiles) issue(g0 + TPG + my_tile);
-    __syncthreads();
-    if (active) {
-      for (int s = 0; s < TPG && g0 + s < ntiles; ++s)
-        compute_tile<NT>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, Lp - (t0 + g0 + s) * TK), qf, st,
-                         P.c, lane);
-    }
-    __syncthreads();                                        // stages are rewritten by the next group / next run
-  }
-  if (active) write_partial<NT>(st, P.po, P.pl, slot, P.R, rowbase, lane);
+__device__ __forceinline__ void cur_load(Cur& c, const int32_t* lens, int cap) {   // values are wavefront-uniform
+  c.u = uni(c.u);
+  c.L = uni(clampi(lens[c.u], 0, cap));
+  c.T = ceil_div(c.L, TK);
+}
+// `by` tiles forward (by <= T - t); runs on into the next non-empty unit; n prompts or sequences
+__device__ __forceinline__ void cur_step(Cur& c, int by, const int32_t* lens, int cap, int n, int Hkv) {
+  c.t = uni(c.t + by);
+  c.j = uni(c.j);
+  if (c.t < c.T) return;
+  c.t = 0;
+  if (++c.j < Hkv) return;
+  c.j = 0;
+  do {
+    if (++c.u >= n) { c.T = 0; c.L = 0; return; }
+    cur_load(c, lens, cap);
+  } while (c.T == 0);
 }
 
-// ---- suffix run: tiles [t0, t0 + ntiles) of unit (b, j); one wavefront, private 16 KB of LDS
-__device__ __forceinline__ void suffix_run(const SharedParams& P, char* wlds, int b, int j, int t0, int ntiles, int Ls,
-                                           int slot, int lane) {
-  const int m16 = lane & 15, g = lane >> 4;
-  const char* kb = P.ks + (size_t)(b * P.Hkv + j) * P.Ls_cap * ROWB;
-  const char* vb = P.vs + (size_t)(b * P.Hkv + j) * P.Ls_cap * ROWB;
+// ---- prefix tiles of one workgroup: `n` tiles of the line starting at `cur`.
+// Tiles are staged in groups of up to WG_WAVES tiles of one unit, one LDS stage each, wavefront v
+// fetching tile v of the group (so the workgroup keeps as many bytes in flight as in the suffix
+// phase).  The R query rows form NRB (a power of two <= 8) blocks of 16; wavefront v computes row
+// block v % NRB on stages [(v / NRB) * NRB, +NRB).  The loads of the next group (also when it
+// belongs to the next unit) are issued in NRB slices between those tile computations, so that the
+// memory pipeline and the matrix pipeline of the CU overlap and no bubble opens at a unit
+// boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
+// merged through LDS and the partial is written.
+template <int NRB, int NT>
+__device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int w, int tid) {
+  const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  constexpr int LPS = 8 / NRB;                              // loads (of K and of V) per slice
+  const int rb = wv & (NRB - 1), part = wv / NRB, s_lo = part * NRB;
+  const int rowbase = 16 * NT * rb;
+  const bool active = rowbase < P.R;
+  const int lrow = lane >> 4, chunk = lane & 15;
+  char* mine = lds + wv * STAGE_B;
 
-  bf16x8 qf[1][4];
-  {
-    const bool ok = m16 < P.r;
-    const char* qp = P.q + ((size_t)b * P.Hq + j * P.r + (ok ? m16 : 0)) * ROWB + 16 * g;
+  u32x4 rk[8], rv[8], qn[NT][4];
+  bf16x8 qf[NT][4];
+  WaveState<NT> st;
+  auto issue_q = [&](const Cur& c) {                        // row = sample * r + head-in-group
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
-      qf[0][ks] = *reinterpret_cast<bf16x8*>(&v);
+    for (int nt = 0; nt < NT; ++nt) {
+      const int row = rowbase + 16 * nt + m16;
+      const bool ok = row < P.R;
+      const int b = c.u * P.G + (ok ? row / P.r : 0), h = c.j * P.r + (ok ? row % P.r : 0);
+      const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) qn[nt][ks] = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
     }
-  }
-  WaveState<1> st;
-  init_state(st);
+  };
+  auto group_size = [&](const Cur& c, int rem) { return min(min(WG_WAVES, c.T - c.t), rem); };
 
-  const int lrow = lane >> 4, chunk = lane & 15;            // instruction i stages rows 4i + lrow: 1 KB contiguous
-  u32x4 rk[8], rv[8];
-  auto issue = [&](int tile) {
-    const int key0 = (t0 + tile) * TK;
-    const int last = min(TK, Ls - key0) - 1;
+  int rem = n, gs = group_size(cur, rem);
+  issue_q(cur);
+  if (wv < gs) {
+    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
+    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
+    const int key0 = (cur.t + wv) * TK, last = min(TK, cur.L - key0) - 1;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
       rk[i] = ldg16(kb + off);
       rv[i] = ldg16(vb + off);
     }
-  };
-  issue(0);
-  for (int tt = 0; tt < ntiles; ++tt) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      lds_st128(wlds + k_off(4 * i + lrow, chunk), rk[i]);
-      lds_st128(wlds + TILE_B + v_off(4 * i + lrow, chunk), rv[i]);
-    }
-    if (tt + 1 < ntiles) issue(tt + 1);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    compute_tile<1>(wlds, wlds + TILE_B, min(TK, Ls - (t0 + tt) * TK), qf, st, P.c, lane);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
-  write_partial<1>(st, P.so, P.sl, slot, P.r, 0, lane);
+  bool fresh = true;
+  while (rem > 0) {
+    wait_vmem();
+    if (wv < gs) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        lds_st128(mine + k_off(4 * i + lrow, chunk), rk[i]);
+        lds_st128(mine + TILE_B + v_off(4 * i + lrow, chunk), rv[i]);
+      }
+    }
+    if (fresh) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qf[nt][ks] = *reinterpret_cast<bf16x8*>(&qn[nt][ks]);
+      init_state(st);
+    }
+    Cur nxt = cur;
+    const int rem2 = rem - gs;
+    int ngs = 0;
+    bool next_fresh = false;
+    if (rem2 > 0) {
+      cur_step(nxt, gs, P.plens, P.Lp_cap, P.P, P.Hkv);
+      ngs = group_size(nxt, rem2);
+      next_fresh = nxt.u != cur.u || nxt.j != cur.j;
+    }
+    lds_barrier();
+    if (next_fresh) issue_q(nxt);
+    const bool more = wv < ngs;                             // this wavefront fetches a tile of the next group
+    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
+    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
+    const int key0 = (nxt.t + wv) * TK, last = min(TK, nxt.L - key0) - 1;
+    // the upper half of the wavefronts issues a slice before each tile computation, the lower half
+    // after it, so that they alternate between the memory pipeline and the matrix pipeline
+    const bool first = wv >= WG_WAVES / 2;
+    auto slice = [&](int k) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {                         // rows past the length re-read the last real row
+        if (i >= k * LPS && i < (k + 1) * LPS) {
+          const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+          rk[i] = ldg16(kb + off);
+          rv[i] = ldg16(vb + off);
+        }
+      }
+    };
+#pragma unroll
+    for (int k = 0; k < NRB; ++k) {
+      const int s = s_lo + k;
+      if (more && first) slice(k);
+      if (active && s < gs)
+        compute_tile<NT>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, cur.L - (cur.t + s) * TK), qf, st,
+                        P.c, lane);
+      if (more && !first) slice(k);
+    }
+    lds_barrier();                                          // stages are rewritten by the next group
+    if (rem2 == 0 || next_fresh) {                          // the unit's run ends here
+      // parts > 0 park their state in their own stage, lane-major (the part-0 wavefront reads with
+      // the same lane index), then part 0 folds them in
+      if (NRB < WG_WAVES) {
+        float* park = reinterpret_cast<float*>(mine);
+        constexpr int PW = 35 * 64;                         // floats parked per row block
+        if (part > 0 && active) {
+#pragma unroll
+          for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+              for (int x = 0; x < 4; ++x) park[nt * PW + (ct * 4 + x) * 64 + lane] = st.O[nt][ct][x];
+            park[nt * PW + 32 * 64 + lane] = st.m[nt];
+            park[nt * PW + 33 * 64 + lane] = st.l[nt];
+            park[nt * PW + 34 * 64 + lane] = st.lr[nt];
+          }
+        }
+        lds_barrier();
+        if (part == 0 && active) {
+          for (int pp = 1; pp < WG_WAVES / NRB; ++pp) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+              const float* o = reinterpret_cast<const float*>(lds + (pp * NRB + rb) * STAGE_B) + nt * PW;
+              const float m2 = o[32 * 64 + lane];
+              if (__all(m2 == -INFINITY)) continue;         // that wavefront had no tile in this run
+              const float mn = fmaxf(st.m[nt], m2);
+              const float a1 = __builtin_amdgcn_exp2f(st.m[nt] - mn), a2 = __builtin_amdgcn_exp2f(m2 - mn);
+#pragma unroll
+              for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                  st.O[nt][ct][x] = st.O[nt][ct][x] * a1 + o[(ct * 4 + x) * 64 + lane] * a2;
+              st.l[nt] = st.l[nt] * a1 + o[33 * 64 + lane] * a2;
+              st.lr[nt] = st.lr[nt] * a1 + o[34 * 64 + lane] * a2;
+              st.m[nt] = mn;
+            }
+          }
+        }
+        lds_barrier();                                      // parked state is dead before tiles are stored again
+      }
+      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.Hkv + cur.j + w, P.R, rowbase, lane);
+    }
+    fresh = next_fresh; cur = nxt; rem = rem2; gs = ngs;
+  }
 }
 
-template <int NTP>
+// ---- suffix tiles of one wavefront: `n` tiles of the line starting at `cur`, streamed through the
+// wavefront's private 16 KB of LDS.  The loads of tile i + 1 (and the query rows of its unit when
+// it starts a new one) are in flight while tile i is computed, across unit boundaries as well.
+__device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds, Cur cur, int n, int slot_base,
+                                              int lane) {
+  const int m16 = lane & 15, g = lane >> 4, lrow = lane >> 4, chunk = lane & 15;
+  u32x4 rk[8], rv[8], qn[4];
+  bf16x8 qf[1][4];
+  WaveState<1> st;
+  auto issue_q = [&](const Cur& c) {
+    const bool ok = m16 < P.r;
+    const char* qp = P.q + ((size_t)c.u * P.Hq + c.j * P.r + (ok ? m16 : 0)) * ROWB + 16 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qn[ks] = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+  };
+  auto issue_tile = [&](const Cur& c) {                     // instruction i stages rows 4i + lrow: 1 KB contiguous
+    const char* kb = P.ks + (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap * ROWB;
+    const char* vb = P.vs + (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap * ROWB;
+    const int key0 = c.t * TK, last = min(TK, c.L - key0) - 1;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {                           // rows past the length re-read the last real row
+      const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+      rk[i] = ldg16(kb + off);
+      rv[i] = ldg16(vb + off);
+    }
+  };
+  issue_q(cur);
+  issue_tile(cur);
+  bool fresh = true;
+  for (int i = 0; i < n; ++i) {
+    wait_vmem();
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      lds_st128(wlds + k_off(4 * k + lrow, chunk), rk[k]);
+      lds_st128(wlds + TILE_B + v_off(4 * k + lrow, chunk), rv[k]);
+    }
+    if (fresh) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) qf[0][ks] = *reinterpret_cast<bf16x8*>(&qn[ks]);
+      init_state(st);
+    }
+    Cur nxt = cur;
+    const bool has_next = i + 1 < n;
+    bool next_fresh = false;
+    if (has_next) {
+      cur_step(nxt, 1, P.slens, P.Ls_cap, P.B, P.Hkv);
+      next_fresh = nxt.u != cur.u || nxt.j != cur.j;
+      if (next_fresh) issue_q(nxt);
+      issue_tile(nxt);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    compute_tile<1>(wlds, wlds + TILE_B, min(TK, cur.L - cur.t * TK), qf, st, P.c, lane);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (!has_next || next_fresh) write_partial<1>(st, P.so, P.sl, cur.u * P.Hkv + cur.j + slot_base, P.r, 0, lane);
+    fresh = next_fresh; cur = nxt;
+  }
+}
+
+template <int NRB, int NT>
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -327,7 +460,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_wg);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_cu);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -343,21 +476,18 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   pp = uni(pp); pj = uni(pj); pt = uni(pt); sb = uni(sb); sj = uni(sj); st0 = uni(st0);
   __syncthreads();                                          // the scan is dead; LDS becomes tile storage
 
-  // ---- prefix tiles of this workgroup (prefix_run ends with a barrier)
-  for_each_run(ilo, ihi, P.P, P.Hkv, pp, pj, pt,
-               [&](int p) { return ceil_div(clampi(P.plens[p], 0, P.Lp_cap), TK); },
-               [&](int p, int j, int t0, int run) {
-                 prefix_run<NTP>(P, lds, p, j, t0, run, clampi(P.plens[p], 0, P.Lp_cap), p * P.Hkv + j + w, tid);
-               });
-
-  // ---- suffix tiles of this wavefront, in its own quarter of the LDS
-  char* wlds = lds + wv * STAGE_B;
-  for_each_run(ka, kb, P.B, P.Hkv, sb, sj, st0,
-               [&](int b) { return ceil_div(clampi(P.slens[b], 0, P.Ls_cap), TK); },
-               [&](int b, int j, int t0, int run) {
-                 suffix_run(P, wlds, b, j, t0, run, clampi(P.slens[b], 0, P.Ls_cap),
-                            b * P.Hkv + j + WG_WAVES * w + wv, lane);
-               });
+  // ---- prefix tiles of this workgroup (ends with a workgroup barrier), then the suffix tiles of
+  // each wavefront in its own stage of the LDS
+  if (ilo < ihi) {
+    Cur c{pp, pj, pt, 0, 0};
+    cur_load(c, P.plens, P.Lp_cap);
+    prefix_stream<NRB, NT>(P, lds, c, ihi - ilo, w, tid);
+  }
+  if (ka < kb) {
+    Cur c{sb, sj, st0, 0, 0};
+    cur_load(c, P.slens, P.Ls_cap);
+    suffix_stream(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * suffix_wg_rank(sc, w) + wv, lane);
+  }
 }
 
 // ---- combine: 32 threads per (sequence, head) row, 4 columns each
@@ -369,7 +499,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_wg);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_cu);
 
   float M = -INFINITY, z = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -387,8 +517,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
     const size_t idx = (size_t)(p * P.Hkv + j + w) * P.R + prow;
     add(P.po + idx * D + c4, P.pl[idx]);
   });
-  for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int w, int v) {
-    const size_t idx = (size_t)(b * P.Hkv + j + WG_WAVES * w + v) * P.r + hi_;
+  for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
+    const size_t idx = (size_t)(b * P.Hkv + j + WG_WAVES * rank + v) * P.r + hi_;
     add(P.so + idx * D + c4, P.sl[idx]);
   });
   const float inv = z > 0.f ? 1.f / z : 0.f;
@@ -402,7 +532,7 @@ struct Layout { size_t cum, pl, po, sl, so, total; };
 
 Layout layout(const rlda_desc& ds) {
   const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, R = r * ds.G;
-  const size_t nps = (size_t)ds.P * ds.Hkv + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
+  const size_t nps = (size_t)ds.P * ds.Hkv + N_CU, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
   size_t o = 0;
   L.cum = o; o = align256(o + (ds.P + B + 1) * 4);
@@ -445,24 +575,28 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
   P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<float*>(ws + L.so);
   P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
-  P.wP = PREFIX_WEIGHT; P.wS = SUFFIX_WEIGHT; P.n_wg = N_WG;
+  P.wP = PREFIX_WEIGHT; P.wS = SUFFIX_WEIGHT; P.n_cu = N_CU;
   if (const char* e = getenv("RLDA_WP")) P.wP = atoi(e);      // TEMP experiment
   if (const char* e = getenv("RLDA_WS")) P.wS = atoi(e);      // TEMP experiment
-  if (const char* e = getenv("RLDA_NWG")) P.n_wg = atoi(e);   // TEMP experiment (<= N_WG)
   P.c = ds.scale * 1.4426950408889634f;
 
-  static bool attr_set = false;                             // 64 KB of dynamic LDS needs an opt-in
+  // 16-row query blocks per wavefront (NT) and wavefronts per prefix tile (NRB, a power of two)
+  const int nt = P.R > 16 * WG_WAVES ? 2 : 1;
+  int nrb = 1;
+  while (16 * nt * nrb < P.R) nrb *= 2;
+  typedef void (*kern_t)(const SharedParams);
+  const kern_t kern = nt == 2 ? partial_kernel<4, 2>
+                      : nrb == 1 ? partial_kernel<1, 1> : nrb == 2 ? partial_kernel<2, 1> : partial_kernel<4, 1>;
+  static bool attr_set = false;                             // more than 64 KB of LDS in total needs an opt-in
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&partial_kernel<1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&partial_kernel<2>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    if (e != hipSuccess) return e;
+    for (kern_t f : {partial_kernel<1, 1>, partial_kernel<2, 1>, partial_kernel<4, 1>, partial_kernel<4, 2>}) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(f),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+      if (e != hipSuccess) return e;
+    }
     attr_set = true;
   }
-  if (P.R <= 64) hipLaunchKernelGGL((partial_kernel<1>), dim3(P.n_wg), dim3(NTHREADS), LDS_BYTES, stream, P);
-  else           hipLaunchKernelGGL((partial_kernel<2>), dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
+  hipLaunchKernelGGL(kern, dim3(2 * P.n_cu), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rows = P.B * P.Hq;

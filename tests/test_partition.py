@@ -50,7 +50,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
                 assert pos == T, (kind, major, j, segs, T)
         assert not seen
     # slots: unique per kind, inside the workspace the library sizes
-    for kind, nslots in ((0, P * Hkv + 512), (1, P * G * Hkv + 4 * 512)):
+    for kind, nslots in ((0, P * Hkv + 256), (1, P * G * Hkv + 8 * 256)):
         sl = runs[runs[:, 0] == kind][:, 7]
         assert len(set(sl.tolist())) == len(sl)
         assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
@@ -58,12 +58,58 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
     key_r = sorted((int(k), int(m), int(j), int(w), int(v), int(s)) for k, m, j, _, _, w, v, s in runs)
     key_p = sorted(tuple(int(x) for x in row) for row in parts)
     assert key_r == key_p
-    # balance: no workgroup holds more than its share + one tile
-    total = int(tp.sum() + ts.sum()) * Hkv
-    share = -(-total // 512) if total else 0
-    load = np.zeros(512, np.int64)
-    np.add.at(load, runs[:, 5], runs[:, 4])
-    assert load.max() <= share + 1
+    # balance: the two workgroups of a pair (w and 256 + w share a compute unit) together hold
+    # an equal share of the prefix tiles and of the suffix tiles, up to rounding
+    npt, nst = int(tp.sum()) * Hkv, int(ts.sum()) * Hkv
+    for kind, total in ((0, npt), (1, nst)):
+        load = np.zeros(256, np.int64)
+        rk = runs[runs[:, 0] == kind]
+        np.add.at(load, rk[:, 5] % 256, rk[:, 4])
+        assert load.sum() == total
+        assert load.max() <= -(-total // 256) and load.min() >= total // 256
+    assert not (runs[(runs[:, 0] == 0)][:, 5] >= 256).any()      # prefix tiles go to the first workgroup of a pair
+    return runs[:nr], parts[:npart.value]
+
+
+def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
+    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens)
+    tp = -(-np.clip(plens, 0, Lp_cap) // TK)
+    ts = -(-np.clip(slens, 0, Ls_cap) // TK)
+    # coverage: each unit's tiles [0, T) are tiled by its runs without gap or overlap
+    for kind, counts in ((0, tp), (1, ts)):
+        rk = runs[runs[:, 0] == kind]
+        seen = {}
+        for _, major, j, t0, n, w, v, slot in rk:
+            assert n > 0
+            seen.setdefault((major, j), []).append((t0, n))
+        for major, T in enumerate(counts):
+            for j in range(Hkv):
+                segs = sorted(seen.pop((major, j), []))
+                pos = 0
+                for t0, n in segs:
+                    assert t0 == pos, (kind, major, j, segs)
+                    pos += n
+                assert pos == T, (kind, major, j, segs, T)
+        assert not seen
+    # slots: unique per kind, inside the workspace the library sizes
+    for kind, nslots in ((0, P * Hkv + 256), (1, P * G * Hkv + 8 * 256)):
+        sl = runs[runs[:, 0] == kind][:, 7]
+        assert len(set(sl.tolist())) == len(sl)
+        assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
+    # the combine enumeration == the set of runs, and per unit in increasing line order
+    key_r = sorted((int(k), int(m), int(j), int(w), int(v), int(s)) for k, m, j, _, _, w, v, s in runs)
+    key_p = sorted(tuple(int(x) for x in row) for row in parts)
+    assert key_r == key_p
+    # balance: the two workgroups of a pair (w and 256 + w share a compute unit) together hold
+    # an equal share of the prefix tiles and of the suffix tiles, up to rounding
+    npt, nst = int(tp.sum()) * Hkv, int(ts.sum()) * Hkv
+    for kind, total in ((0, npt), (1, nst)):
+        load = np.zeros(256, np.int64)
+        rk = runs[runs[:, 0] == kind]
+        np.add.at(load, rk[:, 5] % 256, rk[:, 4])
+        assert load.sum() == total
+        assert load.max() <= -(-total // 256) and load.min() >= total // 256
+    assert not (runs[(runs[:, 0] == 0)][:, 5] >= 256).any()      # prefix tiles go to the first workgroup of a pair
     return runs
 
 
