@@ -104,6 +104,16 @@ typedef struct {
 int rl_decode_attn(const rlda_desc* desc, void* hip_stream);
 
 /*
+ * rl_decode_attn for profiling: additionally records `mid_event` (a hipEvent_t
+ * passed as void*, created by the caller with timing enabled; may be NULL) on
+ * the stream right after the kernel that streams the K/V tensors, i.e. before
+ * the log-sum-exp combine kernel where the path has one.  With events recorded
+ * by the caller before and after the call this gives the duration of that
+ * kernel alone.  Same arguments, return codes and effects otherwise.
+ */
+int rl_decode_attn_profiled(const rlda_desc* desc, void* hip_stream, void* mid_event);
+
+/*
  * Bytes of device workspace rl_decode_attn needs for this descriptor (only the
  * shape fields, dtype and algo are read; no pointer is dereferenced, no device
  * is touched).  Returns 0 if none is needed or if the descriptor is invalid

@@ -52,6 +52,8 @@ class rlda_desc(ctypes.Structure):
 _dp = ctypes.POINTER(rlda_desc)
 _lib.rl_decode_attn.restype = ctypes.c_int
 _lib.rl_decode_attn.argtypes = [_dp, ctypes.c_void_p]
+_lib.rl_decode_attn_profiled.restype = ctypes.c_int
+_lib.rl_decode_attn_profiled.argtypes = [_dp, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rl_decode_attn_workspace_bytes.restype = ctypes.c_size_t
 _lib.rl_decode_attn_workspace_bytes.argtypes = [_dp]
 _lib.rl_decode_attn_plan.restype = ctypes.c_int
@@ -109,6 +111,11 @@ def rl_decode_attn_plan(desc: rlda_desc) -> int:
 def rl_decode_attn_raw(desc: rlda_desc, stream_handle=None) -> int:
     """Direct call; returns the C return code."""
     return _lib.rl_decode_attn(ctypes.byref(desc), stream_handle)
+
+
+def rl_decode_attn_profiled(desc: rlda_desc, stream_handle, mid_event_handle) -> int:
+    """Direct call that also records ``mid_event_handle`` after the K/V-streaming kernel."""
+    return _lib.rl_decode_attn_profiled(ctypes.byref(desc), stream_handle, mid_event_handle)
 
 
 def _torch_dtype_code(t):

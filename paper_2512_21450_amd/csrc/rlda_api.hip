@@ -59,7 +59,20 @@ size_t rl_decode_attn_workspace_bytes(const rlda_desc* desc) {
   return plan(desc) == RLDA_ALGO_SHARED ? rlda::shared_workspace_bytes(*desc) : 0;
 }
 
-int rl_decode_attn(const rlda_desc* desc, void* hip_stream) {
+namespace {
+int enqueue(const rlda_desc* desc, void* hip_stream, void* mid_event);
+}
+
+int rl_decode_attn(const rlda_desc* desc, void* hip_stream) { return enqueue(desc, hip_stream, nullptr); }
+
+int rl_decode_attn_profiled(const rlda_desc* desc, void* hip_stream, void* mid_event) {
+  return enqueue(desc, hip_stream, mid_event);
+}
+
+}  // extern "C"
+
+namespace {
+int enqueue(const rlda_desc* desc, void* hip_stream, void* mid_event) {
   const int pl = plan(desc);
   if (pl < 0) return pl;
   const rlda_desc& ds = *desc;
@@ -76,13 +89,17 @@ int rl_decode_attn(const rlda_desc* desc, void* hip_stream) {
     const size_t need = rlda::shared_workspace_bytes(ds);
     if (need > 0 && (!ds.workspace || ds.workspace_bytes < need)) return RLDA_ERR_WORKSPACE;
     if (need > 0 && (reinterpret_cast<uintptr_t>(ds.workspace) & 255u)) return RLDA_ERR_WORKSPACE;
-    e = rlda::launch_shared(ds, stream);
+    e = rlda::launch_shared(ds, stream, static_cast<hipEvent_t>(mid_event));
   } else {
     e = rlda::launch_simple(ds, stream);
+    if (e == hipSuccess && mid_event) e = hipEventRecord(static_cast<hipEvent_t>(mid_event), stream);
   }
   g_last_hip_error = e;
   return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
 }
+}  // namespace
+
+extern "C" {
 
 int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts, int64_t n_rows, int32_t d,
                    float* out, float* lse, void* hip_stream) {

@@ -15,7 +15,8 @@ hipError_t launch_simple(const rlda_desc& ds, hipStream_t stream);
 // ---- shared-prefix MFMA path (bf16, d = 128)
 bool   shared_supported(const rlda_desc& ds);
 size_t shared_workspace_bytes(const rlda_desc& ds);
-hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream);
+// `mid`, if not null, is recorded between the partial kernel and the combine kernel
+hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid);
 
 // ---- stand-alone log-sum-exp combine over [n_parts, n_rows, d] partials
 hipError_t launch_combine(const float* o_parts, const float* lse_parts, int n_parts, int64_t n_rows,

@@ -1,14 +1,15 @@
 // Shared-prefix decode attention on gfx950 matrix cores (bf16 in, fp32 accumulate, d = 128).
 //
 // Two kernels per call:
-//   partial_kernel  walks the static tile partition of rlda_sched.h.  Prefix tiles
-//                   (the prompt s_0 shared by the K sampled trajectories of a group,
-//                   Algorithm 1 / Sec. 3.2.2 of the paper) are staged once in LDS per
-//                   workgroup and used by all G * Hq/Hkv query rows of the KV group;
-//                   suffix tiles (each trajectory's own generated tokens, Sec. 3.1
-//                   transition s' = (s, a)) are streamed by single wavefronts.
-//   combine_kernel  merges the partial (o, lse) of every (sequence, head) by
-//                   log-sum-exp and writes out / lse.
+//   partial_kernel  walks the static tile partition of rlda_sched.h with two workgroups of four
+//                   wavefronts per compute unit.  Prefix tiles (the prompt s_0 shared by the K
+//                   sampled trajectories of a group, Algorithm 1 / Sec. 3.2.2 of the paper) are
+//                   staged once in LDS per workgroup and used by all G * Hq/Hkv query rows of
+//                   the KV group; suffix tiles (each trajectory's own generated tokens, Sec. 3.1
+//                   transition s' = (s, a)) are streamed by single wavefronts.  Every maximal
+//                   run of tiles of one (prompt or sequence, KV head) yields a partial (o, lse).
+//   combine_kernel  merges the partials of every (sequence, head) by log-sum-exp and writes
+//                   out / lse.
 //
 // Tile math (one wavefront, 16 query rows, 32 keys): scores are produced
 // transposed, S^T = K_tile * Q^T, with v_mfma_f32_16x16x32_bf16 (A = 16 keys x 32
@@ -21,7 +22,6 @@
 // lane until the partial is written.
 #include "rlda_internal.h"
 #include "rlda_sched.h"
-#include <stdlib.h>
 
 namespace rlda {
 namespace {
@@ -561,7 +561,7 @@ bool shared_supported(const rlda_desc& ds) {
 
 size_t shared_workspace_bytes(const rlda_desc& ds) { return layout(ds).total; }
 
-hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
+hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid) {
   const Layout L = layout(ds);
   char* ws = static_cast<char*>(ds.workspace);
   SharedParams P;
@@ -576,8 +576,6 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
   P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
   P.wP = PREFIX_WEIGHT; P.wS = SUFFIX_WEIGHT; P.n_cu = N_CU;
-  if (const char* e = getenv("RLDA_WP")) P.wP = atoi(e);      // TEMP experiment
-  if (const char* e = getenv("RLDA_WS")) P.wS = atoi(e);      // TEMP experiment
   P.c = ds.scale * 1.4426950408889634f;
 
   // 16-row query blocks per wavefront (NT) and wavefronts per prefix tile (NRB, a power of two)
@@ -599,6 +597,10 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream) {
   hipLaunchKernelGGL(kern, dim3(2 * P.n_cu), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (mid) {
+    e = hipEventRecord(mid, stream);
+    if (e != hipSuccess) return e;
+  }
   const int rows = P.B * P.Hq;
   hipLaunchKernelGGL(combine_kernel, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
   return hipGetLastError();
