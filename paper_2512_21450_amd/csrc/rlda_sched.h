@@ -53,11 +53,15 @@ __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, in
   return s;
 }
 
+// Lines are limited to MAX_LINE tiles so that the share arithmetic stays in 32 bits (64-bit
+// division is slow on the GPU and the combine kernel does several per row).
+constexpr int MAX_LINE = (1 << 30) / N_CU;
+
 // pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles
-__host__ __device__ inline int share(int N, int c, int n_cu) { return (int)(((long long)N * c) / n_cu); }
+__host__ __device__ inline int share(int N, int c, int n_cu) { return (int)(((unsigned)N * (unsigned)c) / (unsigned)n_cu); }
 // the pair that owns position i: the largest c with share(N, c) <= i
 __host__ __device__ inline int share_owner(int N, int i, int n_cu) {
-  return (int)((((long long)(i + 1) * n_cu) + N - 1) / N) - 1;
+  return (int)((((unsigned)(i + 1) * (unsigned)n_cu) + (unsigned)N - 1u) / (unsigned)N) - 1;
 }
 
 // prefix tiles [lo, hi) of workgroup w (B workgroups have none)

@@ -192,6 +192,10 @@ __device__ __forceinline__ void write_partial(const WaveState<NT>& st, float* po
 }
 
 __device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
+// K/V rows are read exactly once per call: stream them past the caches
+__device__ __forceinline__ u32x4 ldg16_stream(const char* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
 
 // ---- a position on the work line: unit (u, j), tile t inside it, and the unit's size
 struct Cur { int u, j, t, T, L; };                          // T tiles, L keys
@@ -259,8 +263,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
-      rk[i] = ldg16(kb + off);
-      rv[i] = ldg16(vb + off);
+      rk[i] = ldg16_stream(kb + off);
+      rv[i] = ldg16_stream(vb + off);
     }
   }
   bool fresh = true;
@@ -303,8 +307,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       for (int i = 0; i < 8; ++i) {                         // rows past the length re-read the last real row
         if (i >= k * LPS && i < (k + 1) * LPS) {
           const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
-          rk[i] = ldg16(kb + off);
-          rv[i] = ldg16(vb + off);
+          rk[i] = ldg16_stream(kb + off);
+          rv[i] = ldg16_stream(vb + off);
         }
       }
     };
@@ -387,8 +391,8 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
 #pragma unroll
     for (int i = 0; i < 8; ++i) {                           // rows past the length re-read the last real row
       const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
-      rk[i] = ldg16(kb + off);
-      rv[i] = ldg16(vb + off);
+      rk[i] = ldg16_stream(kb + off);
+      rv[i] = ldg16_stream(vb + off);
     }
   };
   issue_q(cur);
@@ -552,9 +556,8 @@ bool shared_supported(const rlda_desc& ds) {
   const int r = ds.Hq / ds.Hkv;
   if (r > 16 || (int64_t)r * ds.G > 128) return false;                  // rows of one KV group: <= 8 MFMA row blocks
   if (ds.P + B + 1 > MAX_SCAN) return false;                            // the length scan lives in LDS
-  const int64_t tiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) * PREFIX_WEIGHT +
-                        B * ds.Hkv * ceil_div(ds.Ls_cap, TK) * SUFFIX_WEIGHT;
-  if (tiles + N_WG >= (int64_t)1 << 30) return false;                   // 32-bit tile arithmetic
+  if ((int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) > MAX_LINE ||
+      B * ds.Hkv * ceil_div(ds.Ls_cap, TK) > MAX_LINE) return false;       // 32-bit tile arithmetic
   if ((int64_t)ds.Lp_cap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
   return true;
 }
