@@ -494,40 +494,82 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
 }
 
-// ---- combine: 32 threads per (sequence, head) row, 4 columns each
+// ---- combine: 32 lanes per (sequence, head) row.  Lane k of the row first owns part k: all lse
+// values of the row and the first eight parts' values are requested in one round trip; the lse
+// values become weights with two 32-lane reductions; then every lane accumulates its 4 columns.  Parts are taken in line order, so the sum has one fixed order.
 __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
-  const int c4 = (threadIdx.x & 31) * 4;
+  const int sub = threadIdx.x & 31, c4 = sub * 4;
   if (row >= P.B * P.Hq) return;
   const int b = row / P.Hq, h = row % P.Hq;
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
   const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_cu);
-
-  float M = -INFINITY, z = 0.f;
-  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  auto add = [&](const float* o, float l) {                 // online merge; parts arrive in slot order
-    const float Mn = fmaxf(M, l);
-    const float a = __expf(M - Mn), wgt = __expf(l - Mn);
-    const float4 v = *reinterpret_cast<const float4*>(o);
-    z = z * a + wgt;
-    acc.x = acc.x * a + wgt * v.x; acc.y = acc.y * a + wgt * v.y;
-    acc.z = acc.z * a + wgt * v.z; acc.w = acc.w * a + wgt * v.w;
-    M = Mn;
-  };
   const int prow = gs * P.r + hi_;                          // row inside the prefix unit: sample-major
-  for_each_prefix_part(sc, X, P.Hkv, p, j, [&](int w) {
-    const size_t idx = (size_t)(p * P.Hkv + j + w) * P.R + prow;
-    add(P.po + idx * D + c4, P.pl[idx]);
-  });
-  for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
-    const size_t idx = (size_t)(b * P.Hkv + j + WG_WAVES * rank + v) * P.r + hi_;
-    add(P.so + idx * D + c4, P.sl[idx]);
-  });
-  const float inv = z > 0.f ? 1.f / z : 0.f;
+
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  float M = -INFINITY, Z = 0.f;                             // running max and sum over batches of 32 parts
+  for (int base = 0;; base += 32) {
+    // part `base + sub` of this row, as 2 * (row index in its partial array) + [suffix]
+    int n = 0, mine = -1;
+    for_each_prefix_part(sc, X, P.Hkv, p, j, [&](int c) {
+      if (n == base + sub) mine = 2 * ((p * P.Hkv + j + c) * P.R + prow);
+      ++n;
+    });
+    for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
+      if (n == base + sub) mine = 2 * ((b * P.Hkv + j + WG_WAVES * rank + v) * P.r + hi_) + 1;
+      ++n;
+    });
+    const int cnt = min(n - base, 32);
+    if (cnt <= 0) break;
+    // the first 8 parts' values are requested together with the lse values (one round trip)
+    float4 v8[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int id = __shfl(mine, min(u, cnt - 1), 32);
+      v8[u] = *reinterpret_cast<const float4*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D + c4);
+    }
+    const float l = mine < 0 ? -INFINITY : (mine & 1 ? P.sl[mine >> 1] : P.pl[mine >> 1]);
+    float m = l;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 32));
+    const float Mn = fmaxf(M, m);                           // finite: every part holds at least one key
+    const float resc = __expf(M - Mn);
+    const float wgt = __expf(l - Mn);                       // lanes without a part: 0
+    float zs = wgt;
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) zs += __shfl_xor(zs, o, 32);
+    Z = Z * resc + zs;
+    M = Mn;
+    acc.x *= resc; acc.y *= resc; acc.z *= resc; acc.w *= resc;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const float wk = u < cnt ? __shfl(wgt, min(u, cnt - 1), 32) : 0.f;
+      acc.x = fmaf(wk, v8[u].x, acc.x); acc.y = fmaf(wk, v8[u].y, acc.y);
+      acc.z = fmaf(wk, v8[u].z, acc.z); acc.w = fmaf(wk, v8[u].w, acc.w);
+    }
+    for (int k0 = 8; k0 < cnt; k0 += 4) {
+      float4 v[4];
+      float wk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int k = min(k0 + u, cnt - 1);
+        const int id = __shfl(mine, k, 32);
+        wk[u] = k0 + u < cnt ? __shfl(wgt, k, 32) : 0.f;
+        v[u] = *reinterpret_cast<const float4*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D + c4);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        acc.x = fmaf(wk[u], v[u].x, acc.x); acc.y = fmaf(wk[u], v[u].y, acc.y);
+        acc.z = fmaf(wk[u], v[u].z, acc.z); acc.w = fmaf(wk[u], v[u].w, acc.w);
+      }
+    }
+    if (n - base <= 32) break;
+  }
+  const float inv = Z > 0.f ? 1.f / Z : 0.f;
   *reinterpret_cast<float4*>(P.out + (size_t)row * D + c4) = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
-  if (P.lse && c4 == 0) P.lse[row] = z > 0.f ? M + __logf(z) : -INFINITY;
+  if (P.lse && c4 == 0) P.lse[row] = Z > 0.f ? M + __logf(Z) : -INFINITY;
 }
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
