@@ -30,7 +30,7 @@ static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
                     int Ls_cap, double scale, const void* q, const void* kp,
                     const void* vp, const int32_t* plens, const void* ks,
                     const void* vs, const int32_t* slens, int b, int h,
-                    double* out_row, double* lse_val, double* s /* scratch [Lp_cap+Ls_cap] */) {
+                    double* out_row, double* lse_val, double* s /* scratch [Lp_cap+Ls_cap+1+d] */) {
   const int p = b / G;            /* samples of one prompt are adjacent           */
   const int j = h / (Hq / Hkv);   /* contiguous blocks of query heads per KV head */
   const int Lp = clampi(plens[p], 0, Lp_cap);
@@ -40,8 +40,12 @@ static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
   const int64_t poff = ((int64_t)p * Hkv + j) * (int64_t)Lp_cap * d;
   const int64_t soff = ((int64_t)b * Hkv + j) * (int64_t)Ls_cap * d;
 
-  for (int c = 0; c < d; ++c) out_row[c] = 0.0;
+  /* accumulate privately and store once: a row listed twice in `rows` is then written twice
+     with the same values instead of two threads accumulating into the same memory */
+  double* acc = s + (Lp_cap + Ls_cap + 1);
+  for (int c = 0; c < d; ++c) acc[c] = 0.0;
   if (N == 0) {
+    for (int c = 0; c < d; ++c) out_row[c] = 0.0;
     if (lse_val) *lse_val = -INFINITY;
     return;
   }
@@ -62,8 +66,9 @@ static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
     const void* vb = n < Lp ? vp : vs;
     const int64_t vo = n < Lp ? poff + (int64_t)n * d : soff + (int64_t)(n - Lp) * d;
     const double w = exp(s[n] - l);
-    for (int c = 0; c < d; ++c) out_row[c] += w * widen(vb, elem_type, vo + c);
+    for (int c = 0; c < d; ++c) acc[c] += w * widen(vb, elem_type, vo + c);
   }
+  for (int c = 0; c < d; ++c) out_row[c] = acc[c];
   if (lse_val) *lse_val = l;
 }
 
@@ -95,7 +100,7 @@ int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
 #pragma omp single
     used = omp_get_num_threads();
 #endif
-    double* s = (double*)malloc(sizeof(double) * (size_t)(Lp_cap + Ls_cap + 1));
+    double* s = (double*)malloc(sizeof(double) * (size_t)(Lp_cap + Ls_cap + 1 + d));
 #pragma omp for schedule(dynamic, 1)
     for (int64_t i = 0; i < total; ++i) {
       const int b = rows ? rows[2 * i] : (int)(i / Hq);

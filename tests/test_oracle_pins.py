@@ -322,6 +322,11 @@ def test_row_subset_and_thread_count_do_not_change_values():
         np.testing.assert_array_equal(orr[b, h], out[b, h])
         assert lr[b, h] == lse[b, h]
     assert np.isnan(orr[1, 1]).all()
+    # a row listed several times is computed several times, with the same result
+    dup = np.array([[5, 3]] * 6 + [[0, 0]] * 6, np.int32)
+    od, ld = run(x, 0.3, rows=dup, n_threads=4)
+    np.testing.assert_array_equal(od[5, 3], out[5, 3])
+    np.testing.assert_array_equal(od[0, 0], out[0, 0])
 
 
 def test_invalid_arguments_rejected():
