@@ -238,7 +238,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int lrow = lane >> 4, chunk = lane & 15;
   char* mine = lds + wv * STAGE_B;
 
-  u32x4 rk[8], rv[8], qn[NT][4];
+  constexpr bool QPRE = NT == 1;                            // NT = 2 has no registers left for a query prefetch
+  u32x4 rk[8], rv[8], qn[QPRE ? NT : 1][4];
   bf16x8 qf[NT][4];
   WaveState<NT> st;
   auto issue_q = [&](const Cur& c) {                        // row = sample * r + head-in-group
@@ -249,13 +250,16 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       const int b = c.u * P.G + (ok ? row / P.r : 0), h = c.j * P.r + (ok ? row % P.r : 0);
       const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) qn[nt][ks] = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+      for (int ks = 0; ks < 4; ++ks) {
+        const u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+        if (QPRE) qn[nt][ks] = v; else qf[nt][ks] = *reinterpret_cast<const bf16x8*>(&v);
+      }
     }
   };
   auto group_size = [&](const Cur& c, int rem) { return min(min(WG_WAVES, c.T - c.t), rem); };
 
   int rem = n, gs = group_size(cur, rem);
-  issue_q(cur);
+  if (QPRE) issue_q(cur);
   if (wv < gs) {
     const char* kb = P.kp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
     const char* vb = P.vp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
@@ -278,10 +282,15 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       }
     }
     if (fresh) {
+      if (QPRE) {
 #pragma unroll
-      for (int nt = 0; nt < NT; ++nt)
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qf[nt][ks] = *reinterpret_cast<bf16x8*>(&qn[nt][ks]);
+          for (int ks = 0; ks < 4; ++ks) qf[nt][ks] = *reinterpret_cast<bf16x8*>(&qn[nt][ks]);
+      } else {
+        issue_q(cur);
+        wait_vmem();
+      }
       init_state(st);
     }
     Cur nxt = cur;
@@ -294,7 +303,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       next_fresh = nxt.u != cur.u || nxt.j != cur.j;
     }
     lds_barrier();
-    if (next_fresh) issue_q(nxt);
+    if (QPRE && next_fresh) issue_q(nxt);
     const bool more = wv < ngs;                             // this wavefront fetches a tile of the next group
     const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
     const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
