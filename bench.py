@@ -26,6 +26,35 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
+# HBM bytes one launch of the K/V-streaming kernel moved, from two rocprofv3 --pmc passes
+# (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read
+# for the 1 GiB copy of --copy-probe (profiles/partial_kernel_vlm7b_hbm_traffic.md).  Only
+# valid for the workload and the kernel sources the counters were taken on.
+PMC_TRAFFIC = {
+    "workload": "vlm7b",
+    "csrc_sha256": "ab6423e9612181d67bd76a0fb4907a28ea492f4a8430b76553d74d8e9a1ed44a",
+    "fetch_bytes": 623887028,
+    "write_bytes": 18228224,
+}
+
+
+def csrc_sha256():
+    import hashlib
+    d = os.path.join(ROOT, "paper_2512_21450_amd", "csrc")
+    h = hashlib.sha256()
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload, plan):
+    """Counter-measured HBM bytes per launch, or None when they do not describe this run."""
+    if workload != PMC_TRAFFIC["workload"] or plan != 2 or csrc_sha256() != PMC_TRAFFIC["csrc_sha256"]:
+        return None
+    return PMC_TRAFFIC["fetch_bytes"] + PMC_TRAFFIC["write_bytes"]
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -36,6 +65,8 @@ def main():
     ap.add_argument("--algo", default="auto", choices=["auto", "simple", "shared"])
     ap.add_argument("--sets", type=int, default=3, help="rotating copies of the KV tensors")
     ap.add_argument("--event-every", type=int, default=8, help="record per-kernel HIP events on every n-th step")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -84,6 +115,14 @@ def main():
         rc = B.rl_decode_attn_profiled(descs[i % len(descs)], sh, mid)
         if rc != 0:
             raise B.RldaError(rc)
+
+    if args.copy_probe:                       # a plain copy of known size, for calibrating rocprofv3 byte counters
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
     for i in range(args.warmup):
         step(i)
@@ -156,7 +195,7 @@ def main():
         "pct_of_hbm_peak_whole_step": 100.0 * ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes": ab,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, plan),
                      "kernel": "partial_kernel" if plan == 2 else "simple_kernel",
                      "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
                      "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),

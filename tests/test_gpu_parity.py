@@ -248,3 +248,50 @@ def test_lse_combine_against_oracle(d, B):
             assert np.isneginf(lse[r]) and not out[r].any()
         else:
             assert abs(lse[r] - rl) <= 1e-5 and np.abs(out[r] - ro).max() <= 1e-5
+
+
+def test_one_workspace_reused_across_shapes_and_steps(B):
+    """A decode loop reuses one workspace; stale partials of an earlier, larger call must not leak."""
+    import torch
+    big = util.random_case(51, 4, 8, 28, 4, 128, 300, 500, "bf16")
+    small = util.random_case(52, 2, 8, 28, 4, 128, 300, 500, "bf16", plens=[40, 0], slens=[3, 0, 70, 0, 0, 0, 1, 33, 0, 0, 0, 0, 0, 0, 0, 5])
+    tb, tsm = util.to_device(big), util.to_device(small)
+    out_b = torch.empty((32, 28, 128), dtype=torch.float32, device="cuda:0")
+    ds_b = B.desc_from_tensors(tb["q"], tb["k_prefix"], tb["v_prefix"], tb["prefix_lens"], tb["k_suffix"], tb["v_suffix"],
+                               tb["suffix_lens"], 0.1, 8, out_b, None)
+    ws = torch.empty(B.rl_decode_attn_workspace_bytes(ds_b), dtype=torch.uint8, device="cuda:0")
+    ws.fill_(0xFF)                                   # NaN patterns everywhere
+    sh = torch.cuda.current_stream().cuda_stream
+    for t, x, P in ((tb, big, 4), (tsm, small, 2), (tb, big, 4), (tsm, small, 2)):
+        out = torch.empty((P * 8, 28, 128), dtype=torch.float32, device="cuda:0")
+        lse = torch.empty((P * 8, 28), dtype=torch.float32, device="cuda:0")
+        ds = B.desc_from_tensors(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_suffix"], t["v_suffix"],
+                                 t["suffix_lens"], 0.1, 8, out, lse, ws)
+        assert B.rl_decode_attn_workspace_bytes(ds) <= ws.numel()
+        assert B.rl_decode_attn_raw(ds, sh) == 0
+        ro, rl = util.oracle(x, 0.1, 8)
+        util.compare(out, lse, ro, rl, "bf16", f"reused workspace P={P}")
+
+
+def test_profiled_entry_point_records_the_middle_event(B):
+    import torch
+    w = wl.scaled(wl.WORKLOADS["vlm7b"], P=4)
+    x = wl.make_inputs(w)
+    t = util.to_device(x)
+    out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda:0")
+    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda:0")
+    ds = B.desc_from_tensors(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_suffix"], t["v_suffix"],
+                             t["suffix_lens"], w.scale, w.G, out, lse)
+    ws = torch.empty(B.rl_decode_attn_workspace_bytes(ds), dtype=torch.uint8, device="cuda:0")
+    ds.workspace, ds.workspace_bytes = ws.data_ptr(), ws.numel()
+    s = torch.cuda.current_stream()
+    e0, em, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    em.record(s)
+    torch.cuda.synchronize()
+    e0.record(s)
+    assert B.rl_decode_attn_profiled(ds, s.cuda_stream, em.cuda_event) == 0
+    e1.record(s)
+    torch.cuda.synchronize()
+    assert 0.0 < e0.elapsed_time(em) <= e0.elapsed_time(e1)
+    ro, rl = util.oracle(x, w.scale, w.G)
+    util.compare(out, lse, ro, rl, "bf16", "profiled")
