@@ -50,7 +50,6 @@ struct SharedParams {
   float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
-  int wP, wS, n_cu;
   float c;                // scale * log2(e): scores are kept in base 2
 };
 
@@ -195,6 +194,23 @@ __device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast
 // K/V rows are read exactly once per call: stream them past the caches
 __device__ __forceinline__ u32x4 ldg16_stream(const char* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+// locate() of the partition, evaluated by a whole wavefront at once (all lanes active, same
+// arguments): ballots over every 64th entry find the block of 64 entries, a ballot inside the
+// block finds the entry.  Two dependent LDS reads instead of one per bisection step.
+__device__ __forceinline__ void locate_wave(const int* X, int n, int Hkv, int tile, int lane, int& major, int& j,
+                                            int& t) {
+  int cnt = 0;                                              // blocks whose first entry is at or before `tile`
+  for (int b0 = 0; b0 * 64 < n; b0 += 64) {
+    const int i = (b0 + lane) * 64;
+    cnt += __popcll(__ballot(i < n && X[i] * Hkv <= tile));
+  }
+  const int base = (cnt - 1) * 64;                          // cnt >= 1 because X[0] = 0
+  const int i = base + lane;
+  const int lo = base + __popcll(__ballot(i < n && X[i] * Hkv <= tile)) - 1;
+  const int T = X[lo + 1] - X[lo], rem = tile - X[lo] * Hkv;
+  major = lo; j = rem / T; t = rem - j * T;
 }
 
 // ---- a position on the work line: unit (u, j), tile t inside it, and the unit's size
@@ -444,21 +460,21 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   __shared__ int wsum[WG_WAVES];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
 
-  // ---- tile counts of all prompts and sequences, exclusive scan in LDS
+  // ---- tile counts of all prompts and sequences, exclusive scan in LDS: every thread takes a
+  // run of consecutive entries, the runs are chained by a wavefront scan and the wavefront totals
   int* X = reinterpret_cast<int*>(lds);
   const int n = P.P + P.B + 1;
-  for (int i = tid; i < n; i += NTHREADS) {
-    int e = 0;
-    if (i < P.P) e = ceil_div(clampi(P.plens[i], 0, P.Lp_cap), TK);
-    else if (i < P.P + P.B) e = ceil_div(clampi(P.slens[i - P.P], 0, P.Ls_cap), TK);
-    X[i] = e;
-  }
-  __syncthreads();
   {
     const int per = ceil_div(n, NTHREADS);
     const int c0 = min(tid * per, n), c1 = min(c0 + per, n);
     int sum = 0;
-    for (int i = c0; i < c1; ++i) sum += X[i];
+    for (int i = c0; i < c1; ++i) {
+      int e = 0;
+      if (i < P.P) e = ceil_div(clampi(P.plens[i], 0, P.Lp_cap), TK);
+      else if (i < P.P + P.B) e = ceil_div(clampi(P.slens[i - P.P], 0, P.Ls_cap), TK);
+      X[i] = e;                                             // read back below by this thread only
+      sum += e;
+    }
     int incl = sum;
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) {
@@ -473,7 +489,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_cu);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -482,9 +498,9 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   wg_suffix_range(sc, w, klo, khi);
   wave_suffix_range(klo, khi, wv, ka, kb);
   int pp = 0, pj = 0, pt = 0, sb = 0, sj = 0, st0 = 0;
-  if (ilo < ihi) locate(X, P.P, P.Hkv, ilo, pp, pj, pt);
+  if (ilo < ihi) locate_wave(X, P.P, P.Hkv, ilo, lane, pp, pj, pt);
   if (ka < kb) {
-    locate(X + P.P, P.B, P.Hkv, ka + cumP * P.Hkv, sb, sj, st0);   // X + P continues the prompt scan: shift the line
+    locate_wave(X + P.P, P.B, P.Hkv, ka + cumP * P.Hkv, lane, sb, sj, st0);   // X + P continues the prompt scan: shift the line
   }
   pp = uni(pp); pj = uni(pj); pt = uni(pt); sb = uni(sb); sj = uni(sj); st0 = uni(st0);
   __syncthreads();                                          // the scan is dead; LDS becomes tile storage
@@ -514,7 +530,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, P.wP, P.wS, P.n_cu);
+  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   const int prow = gs * P.r + hi_;                          // row inside the prefix unit: sample-major
 
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -629,7 +645,6 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid
   P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<float*>(ws + L.so);
   P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
-  P.wP = PREFIX_WEIGHT; P.wS = SUFFIX_WEIGHT; P.n_cu = N_CU;
   P.c = ds.scale * 1.4426950408889634f;
 
   // 16-row query blocks per wavefront (NT) and wavefronts per prefix tile (NRB, a power of two)
@@ -648,7 +663,7 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid
     }
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(2 * P.n_cu), dim3(NTHREADS), LDS_BYTES, stream, P);
+  hipLaunchKernelGGL(kern, dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (mid) {
