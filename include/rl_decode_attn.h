@@ -141,6 +141,66 @@ const char* rl_decode_attn_last_hip_error(void);
 int rl_decode_attn_version(void);
 
 /*
+ * ---- Paged suffix store, finished trajectories ------------------------------
+ *
+ * A rollout is T consecutive decode actions (Sec. 2.2, Sec. 3.1 transition
+ * s' = (s, a)): every suffix grows by one token per step and trajectories stop
+ * at different steps (Algorithm 1 samples y_{1:T} per trajectory).  A padded
+ * [B, Hkv, Ls_cap, d] suffix store reserves the maximum length for every
+ * sequence; here the suffix K/V live in fixed-size pages drawn from one pool
+ * and a block table names the pages of each sequence in order, so capacity
+ * follows the live tokens (the decode-side counterpart of the padding-free,
+ * dynamically batched training the paper lists in Sec. 4.4, "Resource-Efficient
+ * Training").  Same result as
+ * rl_decode_attn on the gathered suffix.
+ *
+ * Key n of sequence b's suffix is row n % page_size of page
+ * block_table[b, n / page_size].  A page holds all KV heads:
+ * k_pages / v_pages are [n_pages, Hkv, page_size, d].  page_size is a power of
+ * two >= 32.  Table entries at or beyond ceil(suffix_lens[b] / page_size) are
+ * never read as page ids of live keys and may hold anything; entries that are
+ * used are clamped to [0, n_pages) (a wrong id gives a wrong result, never an
+ * out-of-pool access).  suffix_lens are clamped to [0, max_pages * page_size].
+ *
+ * seq_active (may be NULL = all active): one byte per sequence; 0 marks a
+ * finished trajectory.  Its suffix is not read, out[b] = 0 and lse[b] = -inf
+ * are written for it, and a prompt whose G sequences are all finished has its
+ * prefix skipped as well.
+ *
+ * Other fields, ownership, stream and error behaviour are those of rlda_desc /
+ * rl_decode_attn.  mid_event as in rl_decode_attn_profiled (may be NULL).
+ */
+typedef struct {
+  uint32_t struct_size;        /* = sizeof(rlda_paged_desc)                                       */
+  int32_t  dtype;              /* rlda_dtype                                                     */
+  int32_t  algo;               /* rlda_algo                                                      */
+  int32_t  P, G;
+  int32_t  Hq, Hkv, d;
+  int32_t  Lp_cap;             /* row capacity of the prefix buffers                             */
+  int32_t  page_size;          /* rows per page: 32, 64, 128, ... (power of two)                 */
+  int32_t  max_pages;          /* columns of block_table (>= 0)                                  */
+  int32_t  n_pages;            /* pages in the pool (>= 1 if max_pages > 0)                      */
+  float    scale;
+  const void*    q;            /* [B, Hq, d]                                                     */
+  const void*    k_prefix;     /* [P, Hkv, Lp_cap, d]                                            */
+  const void*    v_prefix;
+  const int32_t* prefix_lens;  /* [P]                                                            */
+  const void*    k_pages;      /* [n_pages, Hkv, page_size, d]                                   */
+  const void*    v_pages;
+  const int32_t* block_table;  /* [B, max_pages] page ids                                        */
+  const int32_t* suffix_lens;  /* [B]                                                            */
+  const uint8_t* seq_active;   /* [B] or NULL                                                    */
+  float*   out;                /* [B, Hq, d] fp32                                                */
+  float*   lse;                /* [B, Hq] fp32; may be NULL                                      */
+  void*    workspace;
+  size_t   workspace_bytes;    /* >= rl_decode_attn_paged_workspace_bytes                        */
+} rlda_paged_desc;
+
+int    rl_decode_attn_paged(const rlda_paged_desc* desc, void* hip_stream, void* mid_event);
+size_t rl_decode_attn_paged_workspace_bytes(const rlda_paged_desc* desc);
+int    rl_decode_attn_paged_plan(const rlda_paged_desc* desc);
+
+/*
  * The log-sum-exp combine step on its own (merge of split-softmax partials):
  * for each of n_rows rows, given n_parts partial results over disjoint key
  * sets, o_parts [n_parts, n_rows, d] fp32 (each already normalised) and

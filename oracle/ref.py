@@ -115,3 +115,40 @@ def lse_combine_ref(o_parts, lse_parts):
     res = np.zeros(1, dtype=np.float64)
     lib.rl_lse_combine_ref_f64(n, d, _ptr(o), _ptr(l), _ptr(out), _ptr(res))
     return out, float(res[0])
+
+
+def gather_pages(pages, block_table, suffix_lens, Ls_cap):
+    """Contiguous suffix store [B, Hkv, Ls_cap, d] from a paged one.
+
+    ``pages`` [n_pages, Hkv, page_size, d]; key n of sequence b is row
+    n % page_size of page block_table[b, n // page_size].  Rows at or beyond
+    suffix_lens[b] are left zero.  Plain indexing, no arithmetic on values.
+    """
+    n_pages, Hkv, ps, d = pages.shape
+    B = block_table.shape[0]
+    out = np.zeros((B, Hkv, Ls_cap, d), dtype=pages.dtype)
+    for b in range(B):
+        L = int(min(max(int(suffix_lens[b]), 0), block_table.shape[1] * ps, Ls_cap))
+        for i in range((L + ps - 1) // ps):
+            rows = min(ps, L - i * ps)
+            out[b, :, i * ps:i * ps + rows, :] = pages[int(block_table[b, i]), :, :rows, :]
+    return out
+
+
+def decode_attn_paged_ref(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
+                          seq_active, scale, G, rows=None, n_threads=0):
+    """The paged-suffix call by its definition: gather every sequence's pages
+    in table order and evaluate the attention of the contiguous layout;
+    sequences marked finished (seq_active[b] == 0) get out = 0, lse = -inf."""
+    ps = k_pages.shape[2]
+    sl = np.clip(np.asarray(suffix_lens, dtype=np.int64), 0, block_table.shape[1] * ps).astype(np.int32)
+    cap = max(int(sl.max(initial=0)), 1)
+    ks = gather_pages(k_pages, block_table, sl, cap)
+    vs = gather_pages(v_pages, block_table, sl, cap)
+    out, lse = decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, ks, vs, sl, scale, G, rows=rows,
+                               n_threads=n_threads)
+    if seq_active is not None:
+        dead = np.asarray(seq_active) == 0
+        out[dead] = 0.0
+        lse[dead] = -np.inf
+    return out, lse

@@ -159,3 +159,39 @@ def algorithmic_bytes(w: Workload, prefix_lens, suffix_lens) -> dict:
     suffix = int(np.sum(suffix_lens, dtype=np.int64)) * row
     io = w.B * w.Hq * w.d * w.elem_bytes + w.B * w.Hq * w.d * 4 + w.B * w.Hq * 4 + 4 * (w.P + w.B)
     return {"prefix": prefix, "suffix": suffix, "io": io, "total": prefix + suffix + io}
+
+
+def to_pages(x: dict, page_size: int, seed: int, spare_pages: int = 3, poison: bool = True) -> dict:
+    """Re-house the suffix K/V of a batch in a shuffled page pool (layout only).
+
+    Returns a copy of ``x`` without k_suffix / v_suffix and with
+    ``k_pages`` / ``v_pages`` [n_pages, Hkv, page_size, d], ``block_table``
+    [B, max_pages] (int32) and ``page_size``.  Every sequence gets
+    ceil(len / page_size) pages, assigned in a seeded random order over the
+    pool, which also holds ``spare_pages`` unused pages.  With ``poison`` all
+    rows that hold no live key (tails of last pages, spare pages) are NaN and
+    unused table entries are -1, so that a reader that strays is caught.
+    """
+    ks, vs, sl = x["k_suffix"], x["v_suffix"], np.asarray(x["suffix_lens"])
+    B, Hkv, Ls_cap, d = ks.shape
+    L = np.clip(sl, 0, Ls_cap)
+    need = (L + page_size - 1) // page_size
+    n_pages = int(need.sum()) + spare_pages
+    max_pages = max((Ls_cap + page_size - 1) // page_size, 1)
+    order = np.random.default_rng(seed).permutation(n_pages)
+    nan_bits = np.uint16(0x7FC0) if ks.dtype == np.uint16 else np.float32(np.nan)
+    fill = nan_bits if poison else ks.dtype.type(0)
+    kp = np.full((n_pages, Hkv, page_size, d), fill, dtype=ks.dtype)
+    vp = np.full((n_pages, Hkv, page_size, d), fill, dtype=vs.dtype)
+    table = np.full((B, max_pages), -1 if poison else 0, dtype=np.int32)
+    nxt = 0
+    for b in range(B):
+        for i in range(int(need[b])):
+            pg = int(order[nxt]); nxt += 1
+            rows = min(page_size, int(L[b]) - i * page_size)
+            kp[pg, :, :rows] = ks[b, :, i * page_size:i * page_size + rows]
+            vp[pg, :, :rows] = vs[b, :, i * page_size:i * page_size + rows]
+            table[b, i] = pg
+    y = {k: v for k, v in x.items() if k not in ("k_suffix", "v_suffix")}
+    y.update(k_pages=kp, v_pages=vp, block_table=table, page_size=page_size)
+    return y
