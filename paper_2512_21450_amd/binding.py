@@ -49,7 +49,33 @@ class rlda_desc(ctypes.Structure):
     ]
 
 
+class rlda_paged_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("algo", ctypes.c_int32),
+        ("P", ctypes.c_int32), ("G", ctypes.c_int32),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("Lp_cap", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32), ("n_pages", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("q", ctypes.c_void_p),
+        ("k_prefix", ctypes.c_void_p), ("v_prefix", ctypes.c_void_p), ("prefix_lens", ctypes.c_void_p),
+        ("k_pages", ctypes.c_void_p), ("v_pages", ctypes.c_void_p), ("block_table", ctypes.c_void_p),
+        ("suffix_lens", ctypes.c_void_p), ("seq_active", ctypes.c_void_p),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
 _dp = ctypes.POINTER(rlda_desc)
+_pp = ctypes.POINTER(rlda_paged_desc)
+_lib.rl_decode_attn_paged.restype = ctypes.c_int
+_lib.rl_decode_attn_paged.argtypes = [_pp, ctypes.c_void_p, ctypes.c_void_p]
+_lib.rl_decode_attn_paged_workspace_bytes.restype = ctypes.c_size_t
+_lib.rl_decode_attn_paged_workspace_bytes.argtypes = [_pp]
+_lib.rl_decode_attn_paged_plan.restype = ctypes.c_int
+_lib.rl_decode_attn_paged_plan.argtypes = [_pp]
 _lib.rl_decode_attn.restype = ctypes.c_int
 _lib.rl_decode_attn.argtypes = [_dp, ctypes.c_void_p]
 _lib.rl_decode_attn_profiled.restype = ctypes.c_int
@@ -174,6 +200,86 @@ def rl_decode_attn(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffi
             ds.workspace, ds.workspace_bytes = workspace.data_ptr(), need
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
     rc = _lib.rl_decode_attn(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse
+
+
+def make_paged_desc(dtype, P, G, Hq, Hkv, d, Lp_cap, page_size, max_pages, n_pages, scale,
+                    algo=RLDA_ALGO_AUTO, **ptrs) -> rlda_paged_desc:
+    """Fill a paged descriptor from plain integers; pointer fields default to NULL."""
+    ds = rlda_paged_desc()
+    ds.struct_size = ctypes.sizeof(rlda_paged_desc)
+    ds.dtype, ds.algo = dtype, algo
+    ds.P, ds.G, ds.Hq, ds.Hkv, ds.d, ds.Lp_cap = P, G, Hq, Hkv, d, Lp_cap
+    ds.page_size, ds.max_pages, ds.n_pages = page_size, max_pages, n_pages
+    ds.scale = scale
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_decode_attn_paged_workspace_bytes(desc: rlda_paged_desc) -> int:
+    return _lib.rl_decode_attn_paged_workspace_bytes(ctypes.byref(desc))
+
+
+def rl_decode_attn_paged_plan(desc: rlda_paged_desc) -> int:
+    return _lib.rl_decode_attn_paged_plan(ctypes.byref(desc))
+
+
+def rl_decode_attn_paged_raw(desc: rlda_paged_desc, stream_handle=None, mid_event_handle=None) -> int:
+    """Direct call; returns the C return code."""
+    return _lib.rl_decode_attn_paged(ctypes.byref(desc), stream_handle, mid_event_handle)
+
+
+def paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
+                            scale, G, out, lse=None, seq_active=None, workspace=None,
+                            algo=RLDA_ALGO_AUTO) -> rlda_paged_desc:
+    """Paged descriptor over torch device tensors (shapes as in the header)."""
+    import torch
+    B, Hq, d = q.shape
+    P, Hkv, Lp_cap, _ = k_prefix.shape
+    n_pages, Hkv2, page_size, _ = k_pages.shape
+    if B != P * G or Hkv2 != Hkv or block_table.shape[0] != B or k_pages.shape != v_pages.shape:
+        raise ValueError("inconsistent shapes")
+    if block_table.dtype != torch.int32 or (seq_active is not None and seq_active.dtype != torch.uint8):
+        raise TypeError("block_table must be int32 and seq_active uint8")
+    for t in (q, k_prefix, v_prefix, k_pages, v_pages, prefix_lens, suffix_lens, block_table, out):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    code = _torch_dtype_code(q)
+    for t in (k_prefix, v_prefix, k_pages, v_pages):
+        if _torch_dtype_code(t) != code:
+            raise TypeError("q/k/v dtypes differ")
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    return make_paged_desc(code, P, G, Hq, Hkv, d, Lp_cap, page_size, block_table.shape[1], n_pages, float(scale),
+                           algo, q=ptr(q), k_prefix=ptr(k_prefix), v_prefix=ptr(v_prefix),
+                           prefix_lens=ptr(prefix_lens), k_pages=ptr(k_pages), v_pages=ptr(v_pages),
+                           block_table=ptr(block_table), suffix_lens=ptr(suffix_lens), seq_active=ptr(seq_active),
+                           out=ptr(out), lse=ptr(lse), workspace=ptr(workspace),
+                           workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+
+
+def rl_decode_attn_paged(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens, scale, G,
+                         seq_active=None, out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None):
+    """One decode step over a paged suffix store; returns (out, lse).  Asynchronous on ``stream``."""
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_decode_attn_paged needs device tensors; there is no CPU path")
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    ds = paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
+                                 scale, G, out, lse, seq_active, workspace, algo)
+    if workspace is None:
+        need = rl_decode_attn_paged_workspace_bytes(ds)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+            ds.workspace, ds.workspace_bytes = workspace.data_ptr(), need
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_decode_attn_paged(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream), None)
     if rc != RLDA_OK:
         raise RldaError(rc)
     return out, lse

@@ -8,30 +8,110 @@
 
 namespace {
 
-int check_shape(const rlda_desc* ds) {
+using rlda::Problem;
+
+// Descriptor -> Problem.  Returns RLDA_OK or the error the descriptor itself shows.
+int to_problem(const rlda_desc* ds, Problem& pb) {
   if (!ds) return RLDA_ERR_INVALID;
   if (ds->struct_size != sizeof(rlda_desc)) return RLDA_ERR_STRUCT_SIZE;
-  if (ds->P < 0 || ds->G < 0 || ds->Hq <= 0 || ds->Hkv <= 0 || ds->d <= 0 || ds->Lp_cap < 0 || ds->Ls_cap < 0)
-    return RLDA_ERR_INVALID;
-  if (ds->dtype != RLDA_F32 && ds->dtype != RLDA_BF16) return RLDA_ERR_UNSUPPORTED;
-  if (ds->algo != RLDA_ALGO_AUTO && ds->algo != RLDA_ALGO_SIMPLE && ds->algo != RLDA_ALGO_SHARED)
-    return RLDA_ERR_UNSUPPORTED;
-  if (ds->d != 64 && ds->d != 128) return RLDA_ERR_UNSUPPORTED;
-  if (ds->Hq % ds->Hkv != 0) return RLDA_ERR_UNSUPPORTED;
-  // index arithmetic in the kernels is 32-bit for (sequence, head) counts
-  if ((int64_t)ds->P * ds->G * ds->Hq > (int64_t)1 << 30) return RLDA_ERR_UNSUPPORTED;
+  pb = Problem{};
+  pb.dtype = ds->dtype; pb.algo = ds->algo;
+  pb.P = ds->P; pb.G = ds->G; pb.Hq = ds->Hq; pb.Hkv = ds->Hkv; pb.d = ds->d;
+  pb.Lp_cap = ds->Lp_cap; pb.Ls_cap = ds->Ls_cap; pb.scale = ds->scale;
+  pb.q = ds->q; pb.k_prefix = ds->k_prefix; pb.v_prefix = ds->v_prefix; pb.prefix_lens = ds->prefix_lens;
+  pb.k_suffix = ds->k_suffix; pb.v_suffix = ds->v_suffix; pb.suffix_lens = ds->suffix_lens;
+  pb.out = ds->out; pb.lse = ds->lse; pb.workspace = ds->workspace; pb.workspace_bytes = ds->workspace_bytes;
   return RLDA_OK;
 }
 
-int plan(const rlda_desc* ds) {
-  const int rc = check_shape(ds);
+int to_problem(const rlda_paged_desc* ds, Problem& pb) {
+  if (!ds) return RLDA_ERR_INVALID;
+  if (ds->struct_size != sizeof(rlda_paged_desc)) return RLDA_ERR_STRUCT_SIZE;
+  if (ds->max_pages < 0 || ds->n_pages < 0 || ds->page_size <= 0) return RLDA_ERR_INVALID;
+  if (ds->page_size < 32 || (ds->page_size & (ds->page_size - 1))) return RLDA_ERR_UNSUPPORTED;
+  if ((int64_t)ds->max_pages * ds->page_size > (int64_t)1 << 30) return RLDA_ERR_UNSUPPORTED;
+  if (ds->max_pages > 0 && ds->n_pages < 1) return RLDA_ERR_INVALID;
+  pb = Problem{};
+  pb.dtype = ds->dtype; pb.algo = ds->algo;
+  pb.P = ds->P; pb.G = ds->G; pb.Hq = ds->Hq; pb.Hkv = ds->Hkv; pb.d = ds->d;
+  pb.Lp_cap = ds->Lp_cap; pb.Ls_cap = ds->max_pages * ds->page_size; pb.scale = ds->scale;
+  pb.q = ds->q; pb.k_prefix = ds->k_prefix; pb.v_prefix = ds->v_prefix; pb.prefix_lens = ds->prefix_lens;
+  pb.k_suffix = ds->k_pages; pb.v_suffix = ds->v_pages; pb.suffix_lens = ds->suffix_lens;
+  pb.block_table = ds->block_table;
+  pb.page_shift = __builtin_ctz((unsigned)ds->page_size);
+  pb.max_pages = ds->max_pages; pb.n_pages = ds->n_pages;
+  pb.seq_active = ds->seq_active;
+  pb.out = ds->out; pb.lse = ds->lse; pb.workspace = ds->workspace; pb.workspace_bytes = ds->workspace_bytes;
+  return RLDA_OK;
+}
+
+int check_shape(const Problem& pb) {
+  if (pb.P < 0 || pb.G < 0 || pb.Hq <= 0 || pb.Hkv <= 0 || pb.d <= 0 || pb.Lp_cap < 0 || pb.Ls_cap < 0)
+    return RLDA_ERR_INVALID;
+  if (pb.dtype != RLDA_F32 && pb.dtype != RLDA_BF16) return RLDA_ERR_UNSUPPORTED;
+  if (pb.algo != RLDA_ALGO_AUTO && pb.algo != RLDA_ALGO_SIMPLE && pb.algo != RLDA_ALGO_SHARED)
+    return RLDA_ERR_UNSUPPORTED;
+  if (pb.d != 64 && pb.d != 128) return RLDA_ERR_UNSUPPORTED;
+  if (pb.Hq % pb.Hkv != 0) return RLDA_ERR_UNSUPPORTED;
+  // index arithmetic in the kernels is 32-bit for (sequence, head) counts
+  if ((int64_t)pb.P * pb.G * pb.Hq > (int64_t)1 << 30) return RLDA_ERR_UNSUPPORTED;
+  return RLDA_OK;
+}
+
+int plan(const Problem& pb) {
+  const int rc = check_shape(pb);
   if (rc != RLDA_OK) return rc;
-  if (ds->algo == RLDA_ALGO_SIMPLE) return RLDA_ALGO_SIMPLE;
-  if (rlda::shared_supported(*ds)) return RLDA_ALGO_SHARED;
-  return ds->algo == RLDA_ALGO_SHARED ? RLDA_ERR_UNSUPPORTED : RLDA_ALGO_SIMPLE;
+  if (pb.algo == RLDA_ALGO_SIMPLE) return RLDA_ALGO_SIMPLE;
+  if (rlda::shared_supported(pb)) return RLDA_ALGO_SHARED;
+  return pb.algo == RLDA_ALGO_SHARED ? RLDA_ERR_UNSUPPORTED : RLDA_ALGO_SIMPLE;
+}
+
+template <class Desc>
+int plan_of(const Desc* desc) {
+  Problem pb;
+  const int rc = to_problem(desc, pb);
+  return rc != RLDA_OK ? rc : plan(pb);
+}
+
+template <class Desc>
+size_t workspace_of(const Desc* desc) {
+  Problem pb;
+  if (to_problem(desc, pb) != RLDA_OK) return 0;
+  return plan(pb) == RLDA_ALGO_SHARED ? rlda::shared_workspace_bytes(pb) : 0;
 }
 
 thread_local hipError_t g_last_hip_error = hipSuccess;
+
+int enqueue(const Problem& pb, void* hip_stream, void* mid_event) {
+  const int pl = plan(pb);
+  if (pl < 0) return pl;
+  const int64_t B = (int64_t)pb.P * pb.G;
+  if (B > 0 && (!pb.q || !pb.prefix_lens || !pb.suffix_lens || !pb.out)) return RLDA_ERR_INVALID;
+  if (pb.P > 0 && pb.Lp_cap > 0 && (!pb.k_prefix || !pb.v_prefix)) return RLDA_ERR_INVALID;
+  if (B > 0 && pb.Ls_cap > 0 && (!pb.k_suffix || !pb.v_suffix)) return RLDA_ERR_INVALID;
+  if (B > 0 && pb.max_pages > 0 && !pb.block_table) return RLDA_ERR_INVALID;
+  if (B == 0) return RLDA_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (pl == RLDA_ALGO_SHARED) {
+    const size_t need = rlda::shared_workspace_bytes(pb);
+    if (need > 0 && (!pb.workspace || pb.workspace_bytes < need)) return RLDA_ERR_WORKSPACE;
+    if (need > 0 && (reinterpret_cast<uintptr_t>(pb.workspace) & 255u)) return RLDA_ERR_WORKSPACE;
+    e = rlda::launch_shared(pb, stream, static_cast<hipEvent_t>(mid_event));
+  } else {
+    e = rlda::launch_simple(pb, stream);
+    if (e == hipSuccess && mid_event) e = hipEventRecord(static_cast<hipEvent_t>(mid_event), stream);
+  }
+  g_last_hip_error = e;
+  return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
+}
+
+template <class Desc>
+int enqueue_of(const Desc* desc, void* hip_stream, void* mid_event) {
+  Problem pb;
+  const int rc = to_problem(desc, pb);
+  return rc != RLDA_OK ? rc : enqueue(pb, hip_stream, mid_event);
+}
 
 }  // namespace
 
@@ -39,7 +119,7 @@ extern "C" {
 
 const char* rl_decode_attn_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
-int rl_decode_attn_version(void) { return 100; }
+int rl_decode_attn_version(void) { return 200; }
 
 const char* rl_decode_attn_strerror(int code) {
   switch (code) {
@@ -53,51 +133,20 @@ const char* rl_decode_attn_strerror(int code) {
   }
 }
 
-int rl_decode_attn_plan(const rlda_desc* desc) { return plan(desc); }
-
-size_t rl_decode_attn_workspace_bytes(const rlda_desc* desc) {
-  return plan(desc) == RLDA_ALGO_SHARED ? rlda::shared_workspace_bytes(*desc) : 0;
-}
-
-namespace {
-int enqueue(const rlda_desc* desc, void* hip_stream, void* mid_event);
-}
-
-int rl_decode_attn(const rlda_desc* desc, void* hip_stream) { return enqueue(desc, hip_stream, nullptr); }
-
+int rl_decode_attn_plan(const rlda_desc* desc) { return plan_of(desc); }
+size_t rl_decode_attn_workspace_bytes(const rlda_desc* desc) { return workspace_of(desc); }
+int rl_decode_attn(const rlda_desc* desc, void* hip_stream) { return enqueue_of(desc, hip_stream, nullptr); }
 int rl_decode_attn_profiled(const rlda_desc* desc, void* hip_stream, void* mid_event) {
-  return enqueue(desc, hip_stream, mid_event);
+  return enqueue_of(desc, hip_stream, mid_event);
+}
+
+int rl_decode_attn_paged_plan(const rlda_paged_desc* desc) { return plan_of(desc); }
+size_t rl_decode_attn_paged_workspace_bytes(const rlda_paged_desc* desc) { return workspace_of(desc); }
+int rl_decode_attn_paged(const rlda_paged_desc* desc, void* hip_stream, void* mid_event) {
+  return enqueue_of(desc, hip_stream, mid_event);
 }
 
 }  // extern "C"
-
-namespace {
-int enqueue(const rlda_desc* desc, void* hip_stream, void* mid_event) {
-  const int pl = plan(desc);
-  if (pl < 0) return pl;
-  const rlda_desc& ds = *desc;
-  const int64_t B = (int64_t)ds.P * ds.G;
-  if (!ds.q || !ds.prefix_lens || !ds.suffix_lens || !ds.out) {
-    if (B > 0) return RLDA_ERR_INVALID;
-  }
-  if (ds.P > 0 && ds.Lp_cap > 0 && (!ds.k_prefix || !ds.v_prefix)) return RLDA_ERR_INVALID;
-  if (B > 0 && ds.Ls_cap > 0 && (!ds.k_suffix || !ds.v_suffix)) return RLDA_ERR_INVALID;
-  if (B == 0) return RLDA_OK;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  hipError_t e;
-  if (pl == RLDA_ALGO_SHARED) {
-    const size_t need = rlda::shared_workspace_bytes(ds);
-    if (need > 0 && (!ds.workspace || ds.workspace_bytes < need)) return RLDA_ERR_WORKSPACE;
-    if (need > 0 && (reinterpret_cast<uintptr_t>(ds.workspace) & 255u)) return RLDA_ERR_WORKSPACE;
-    e = rlda::launch_shared(ds, stream, static_cast<hipEvent_t>(mid_event));
-  } else {
-    e = rlda::launch_simple(ds, stream);
-    if (e == hipSuccess && mid_event) e = hipEventRecord(static_cast<hipEvent_t>(mid_event), stream);
-  }
-  g_last_hip_error = e;
-  return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
-}
-}  // namespace
 
 extern "C" {
 

@@ -9,14 +9,34 @@
 
 namespace rlda {
 
+// One decode step in the form the kernels take it: the union of rlda_desc (contiguous suffix
+// store) and rlda_paged_desc (page pool + block table, finished-sequence flags).
+struct Problem {
+  int dtype, algo;
+  int P, G, Hq, Hkv, d;
+  int Lp_cap;
+  int Ls_cap;                     // suffix row capacity per sequence (paged: max_pages * page_size)
+  float scale;
+  const void* q;
+  const void* k_prefix; const void* v_prefix; const int32_t* prefix_lens;
+  const void* k_suffix; const void* v_suffix;   // [B, Hkv, Ls_cap, d], or the pools [n_pages, Hkv, page_size, d]
+  const int32_t* suffix_lens;
+  const int32_t* block_table;     // null: contiguous suffix store
+  int page_shift;                 // log2(page_size)
+  int max_pages, n_pages;
+  const uint8_t* seq_active;      // null: every sequence is live
+  float* out; float* lse;
+  void* workspace; size_t workspace_bytes;
+};
+
 // ---- simple path: one wavefront per (sequence, query head); fp32 or bf16; d in {64,128}
-hipError_t launch_simple(const rlda_desc& ds, hipStream_t stream);
+hipError_t launch_simple(const Problem& pb, hipStream_t stream);
 
 // ---- shared-prefix MFMA path (bf16, d = 128)
-bool   shared_supported(const rlda_desc& ds);
-size_t shared_workspace_bytes(const rlda_desc& ds);
+bool   shared_supported(const Problem& pb);
+size_t shared_workspace_bytes(const Problem& pb);
 // `mid`, if not null, is recorded between the partial kernel and the combine kernel
-hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid);
+hipError_t launch_shared(const Problem& pb, hipStream_t stream, hipEvent_t mid);
 
 // ---- stand-alone log-sum-exp combine over [n_parts, n_rows, d] partials
 hipError_t launch_combine(const float* o_parts, const float* lse_parts, int n_parts, int64_t n_rows,

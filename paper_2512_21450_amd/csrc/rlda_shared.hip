@@ -51,7 +51,30 @@ struct SharedParams {
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
   float c;                // scale * log2(e): scores are kept in base 2
+  // extended form only (kernels instantiated with EXT = true):
+  const int32_t* table;   // [B, max_pages] page ids when ks / vs are page pools [n_pages, Hkv, page, D], else null
+  const uint8_t* active;  // [B] finished-sequence flags, or null
+  int page_shift, max_pages, n_pages;
 };
+
+// Effective lengths: clamped to the capacity; in the extended form a finished sequence has no
+// suffix, and a prompt none of whose G sequences is live has no prefix.
+template <bool EXT>
+__device__ __forceinline__ int plen_of(const SharedParams& P, int p) {
+  int L = clampi(P.plens[p], 0, P.Lp_cap);
+  if (EXT && P.active) {
+    bool any = false;
+    for (int g = 0; g < P.G; ++g) any |= P.active[p * P.G + g] != 0;
+    if (!any) L = 0;
+  }
+  return L;
+}
+template <bool EXT>
+__device__ __forceinline__ int slen_of(const SharedParams& P, int b) {
+  int L = clampi(P.slens[b], 0, P.Ls_cap);
+  if (EXT && P.active && P.active[b] == 0) L = 0;
+  return L;
+}
 
 template <int NT>
 struct WaveState {
@@ -216,13 +239,15 @@ __device__ __forceinline__ void locate_wave(const int* X, int n, int Hkv, int ti
 // ---- a position on the work line: unit (u, j), tile t inside it, and the unit's size
 struct Cur { int u, j, t, T, L; };                          // T tiles, L keys
 
-__device__ __forceinline__ void cur_load(Cur& c, const int32_t* lens, int cap) {   // values are wavefront-uniform
+template <class LenOf>
+__device__ __forceinline__ void cur_load(Cur& c, LenOf len_of) {   // values are wavefront-uniform
   c.u = uni(c.u);
-  c.L = uni(clampi(lens[c.u], 0, cap));
+  c.L = uni(len_of(c.u));
   c.T = ceil_div(c.L, TK);
 }
 // `by` tiles forward (by <= T - t); runs on into the next non-empty unit; n prompts or sequences
-__device__ __forceinline__ void cur_step(Cur& c, int by, const int32_t* lens, int cap, int n, int Hkv) {
+template <class LenOf>
+__device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, int Hkv) {
   c.t = uni(c.t + by);
   c.j = uni(c.j);
   if (c.t < c.T) return;
@@ -231,7 +256,7 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, const int32_t* lens, in
   c.j = 0;
   do {
     if (++c.u >= n) { c.T = 0; c.L = 0; return; }
-    cur_load(c, lens, cap);
+    cur_load(c, len_of);
   } while (c.T == 0);
 }
 
@@ -244,8 +269,9 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, const int32_t* lens, in
 // memory pipeline and the matrix pipeline of the CU overlap and no bubble opens at a unit
 // boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
 // merged through LDS and the partial is written.
-template <int NRB, int NT>
+template <int NRB, int NT, bool EXT>
 __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int w, int tid) {
+  auto len_of = [&](int p) { return plen_of<EXT>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   constexpr int LPS = 8 / NRB;                              // loads (of K and of V) per slice
   const int rb = wv & (NRB - 1), part = wv / NRB, s_lo = part * NRB;
@@ -314,7 +340,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
     int ngs = 0;
     bool next_fresh = false;
     if (rem2 > 0) {
-      cur_step(nxt, gs, P.plens, P.Lp_cap, P.P, P.Hkv);
+      cur_step(nxt, gs, len_of, P.P, P.Hkv);
       ngs = group_size(nxt, rem2);
       next_fresh = nxt.u != cur.u || nxt.j != cur.j;
     }
@@ -397,8 +423,10 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
 // ---- suffix tiles of one wavefront: `n` tiles of the line starting at `cur`, streamed through the
 // wavefront's private 16 KB of LDS.  The loads of tile i + 1 (and the query rows of its unit when
 // it starts a new one) are in flight while tile i is computed, across unit boundaries as well.
+template <bool EXT>
 __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds, Cur cur, int n, int slot_base,
                                               int lane) {
+  auto len_of = [&](int b) { return slen_of<EXT>(P, b); };
   const int m16 = lane & 15, g = lane >> 4, lrow = lane >> 4, chunk = lane & 15;
   u32x4 rk[8], rv[8], qn[4];
   bf16x8 qf[1][4];
@@ -410,12 +438,17 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
     for (int ks = 0; ks < 4; ++ks) qn[ks] = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
   };
   auto issue_tile = [&](const Cur& c) {                     // instruction i stages rows 4i + lrow: 1 KB contiguous
-    const char* kb = P.ks + (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap * ROWB;
-    const char* vb = P.vs + (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap * ROWB;
     const int key0 = c.t * TK, last = min(TK, c.L - key0) - 1;
+    size_t row0 = (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap + key0;      // first row of the tile in the store
+    if (EXT && P.table) {                                   // a tile never straddles pages: TK divides the page size
+      const int pg = uni(clampi(P.table[(size_t)c.u * P.max_pages + (key0 >> P.page_shift)], 0, P.n_pages - 1));
+      row0 = (((size_t)pg * P.Hkv + c.j) << P.page_shift) + (key0 & ((1 << P.page_shift) - 1));
+    }
+    const char* kb = P.ks + row0 * ROWB;
+    const char* vb = P.vs + row0 * ROWB;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {                           // rows past the length re-read the last real row
-      const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+      const size_t off = (size_t)min(4 * i + lrow, last) * ROWB + 16 * chunk;
       rk[i] = ldg16_stream(kb + off);
       rv[i] = ldg16_stream(vb + off);
     }
@@ -439,7 +472,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
     const bool has_next = i + 1 < n;
     bool next_fresh = false;
     if (has_next) {
-      cur_step(nxt, 1, P.slens, P.Ls_cap, P.B, P.Hkv);
+      cur_step(nxt, 1, len_of, P.B, P.Hkv);
       next_fresh = nxt.u != cur.u || nxt.j != cur.j;
       if (next_fresh) issue_q(nxt);
       issue_tile(nxt);
@@ -454,7 +487,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   }
 }
 
-template <int NRB, int NT>
+template <int NRB, int NT, bool EXT>
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -470,8 +503,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
     int sum = 0;
     for (int i = c0; i < c1; ++i) {
       int e = 0;
-      if (i < P.P) e = ceil_div(clampi(P.plens[i], 0, P.Lp_cap), TK);
-      else if (i < P.P + P.B) e = ceil_div(clampi(P.slens[i - P.P], 0, P.Ls_cap), TK);
+      if (i < P.P) e = ceil_div(plen_of<EXT>(P, i), TK);
+      else if (i < P.P + P.B) e = ceil_div(slen_of<EXT>(P, i - P.P), TK);
       X[i] = e;                                             // read back below by this thread only
       sum += e;
     }
@@ -509,24 +542,30 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   // each wavefront in its own stage of the LDS
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
-    cur_load(c, P.plens, P.Lp_cap);
-    prefix_stream<NRB, NT>(P, lds, c, ihi - ilo, w, tid);
+    cur_load(c, [&](int p) { return plen_of<EXT>(P, p); });
+    prefix_stream<NRB, NT, EXT>(P, lds, c, ihi - ilo, w, tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
-    cur_load(c, P.slens, P.Ls_cap);
-    suffix_stream(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * suffix_wg_rank(sc, w) + wv, lane);
+    cur_load(c, [&](int b) { return slen_of<EXT>(P, b); });
+    suffix_stream<EXT>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * suffix_wg_rank(sc, w) + wv, lane);
   }
 }
 
 // ---- combine: 32 lanes per (sequence, head) row.  Lane k of the row first owns part k: all lse
 // values of the row and the first eight parts' values are requested in one round trip; the lse
 // values become weights with two 32-lane reductions; then every lane accumulates its 4 columns.  Parts are taken in line order, so the sum has one fixed order.
+template <bool EXT>
 __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
   const int sub = threadIdx.x & 31, c4 = sub * 4;
   if (row >= P.B * P.Hq) return;
   const int b = row / P.Hq, h = row % P.Hq;
+  if (EXT && P.active && P.active[b] == 0) {               // finished sequence: its prefix rows were computed, not used
+    *reinterpret_cast<float4*>(P.out + (size_t)row * D + c4) = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (P.lse && c4 == 0) P.lse[row] = -INFINITY;
+    return;
+  }
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
@@ -601,7 +640,7 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout { size_t cum, pl, po, sl, so, total; };
 
-Layout layout(const rlda_desc& ds) {
+Layout layout(const Problem& ds) {
   const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, R = r * ds.G;
   const size_t nps = (size_t)ds.P * ds.Hkv + N_CU, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
@@ -617,7 +656,7 @@ Layout layout(const rlda_desc& ds) {
 
 }  // namespace
 
-bool shared_supported(const rlda_desc& ds) {
+bool shared_supported(const Problem& ds) {
   if (ds.dtype != RLDA_BF16 || ds.d != D) return false;
   const int64_t B = (int64_t)ds.P * ds.G;
   const int r = ds.Hq / ds.Hkv;
@@ -629,9 +668,9 @@ bool shared_supported(const rlda_desc& ds) {
   return true;
 }
 
-size_t shared_workspace_bytes(const rlda_desc& ds) { return layout(ds).total; }
+size_t shared_workspace_bytes(const Problem& ds) { return layout(ds).total; }
 
-hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid) {
+hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) {
   const Layout L = layout(ds);
   char* ws = static_cast<char*>(ds.workspace);
   SharedParams P;
@@ -651,12 +690,18 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid
   const int nt = P.R > 16 * WG_WAVES ? 2 : 1;
   int nrb = 1;
   while (16 * nt * nrb < P.R) nrb *= 2;
+  P.table = ds.block_table; P.active = ds.seq_active;
+  P.page_shift = ds.page_shift; P.max_pages = ds.max_pages; P.n_pages = ds.n_pages;
+  const bool ext = ds.block_table != nullptr || ds.seq_active != nullptr;
   typedef void (*kern_t)(const SharedParams);
-  const kern_t kern = nt == 2 ? partial_kernel<4, 2>
-                      : nrb == 1 ? partial_kernel<1, 1> : nrb == 2 ? partial_kernel<2, 1> : partial_kernel<4, 1>;
+  static const kern_t kerns[2][4] = {
+      {partial_kernel<1, 1, false>, partial_kernel<2, 1, false>, partial_kernel<4, 1, false>, partial_kernel<4, 2, false>},
+      {partial_kernel<1, 1, true>, partial_kernel<2, 1, true>, partial_kernel<4, 1, true>, partial_kernel<4, 2, true>}};
+  const kern_t kern = kerns[ext][nt == 2 ? 3 : nrb == 1 ? 0 : nrb == 2 ? 1 : 2];
   static bool attr_set = false;                             // more than 64 KB of LDS in total needs an opt-in
   if (!attr_set) {
-    for (kern_t f : {partial_kernel<1, 1>, partial_kernel<2, 1>, partial_kernel<4, 1>, partial_kernel<4, 2>}) {
+    for (int i = 0; i < 8; ++i) {
+      const kern_t f = kerns[i / 4][i % 4];
       const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(f),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
       if (e != hipSuccess) return e;
@@ -671,7 +716,8 @@ hipError_t launch_shared(const rlda_desc& ds, hipStream_t stream, hipEvent_t mid
     if (e != hipSuccess) return e;
   }
   const int rows = P.B * P.Hq;
-  hipLaunchKernelGGL(combine_kernel, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  if (ext) hipLaunchKernelGGL(combine_kernel<true>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  else     hipLaunchKernelGGL(combine_kernel<false>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
   return hipGetLastError();
 }
 

@@ -18,6 +18,9 @@ struct SimpleParams {
   float* out; float* lse;
   int G, Hq, Hkv, Lp_cap, Ls_cap;
   float scale;
+  const int32_t* table;       // paged suffix store: [B, max_pages] page ids, else null
+  int page_shift, max_pages, n_pages;
+  const uint8_t* active;      // finished-sequence flags or null
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
@@ -62,13 +65,15 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
   constexpr int NC = D / 64;                 // output columns per lane
   __shared__ __attribute__((aligned(16))) float q_sh[D];
   __shared__ float p_sh[64];
+  __shared__ size_t r_sh[64];                // element offset of each of the tile's key rows
 
   const int lane = threadIdx.x;
   const int b = blockIdx.x / P.Hq, h = blockIdx.x % P.Hq;
   const int p = b / P.G;
   const int j = h / (P.Hq / P.Hkv);
-  const int Lp = min(max(P.plens[p], 0), P.Lp_cap);
-  const int Ls = min(max(P.slens[b], 0), P.Ls_cap);
+  const bool live = !P.active || P.active[b] != 0;   // a finished sequence has no keys: out = 0, lse = -inf
+  const int Lp = live ? min(max(P.plens[p], 0), P.Lp_cap) : 0;
+  const int Ls = live ? min(max(P.slens[b], 0), P.Ls_cap) : 0;
 
   const T* q = static_cast<const T*>(P.q) + ((size_t)b * P.Hq + h) * D;
   for (int c = lane; c < D; c += 64) q_sh[c] = Vec<T>::one(q + c);
@@ -80,15 +85,26 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
 
   for (int seg = 0; seg < 2; ++seg) {
     const int len = seg == 0 ? Lp : Ls;
+    const bool paged = seg == 1 && P.table != nullptr;
     const T* kb = seg == 0 ? static_cast<const T*>(P.kp) + ((size_t)p * P.Hkv + j) * (size_t)P.Lp_cap * D
+                : paged    ? static_cast<const T*>(P.ks)
                            : static_cast<const T*>(P.ks) + ((size_t)b * P.Hkv + j) * (size_t)P.Ls_cap * D;
     const T* vb = seg == 0 ? static_cast<const T*>(P.vp) + ((size_t)p * P.Hkv + j) * (size_t)P.Lp_cap * D
+                : paged    ? static_cast<const T*>(P.vs)
                            : static_cast<const T*>(P.vs) + ((size_t)b * P.Hkv + j) * (size_t)P.Ls_cap * D;
     for (int n0 = 0; n0 < len; n0 += 64) {
       const int cnt = min(64, len - n0);
       float s = -INFINITY;
+      __syncthreads();                                    // r_sh of the previous tile is no longer read
       if (lane < cnt) {
-        const T* kr = kb + (size_t)(n0 + lane) * D;
+        const int n = n0 + lane;
+        size_t row = (size_t)n;
+        if (paged) {                                      // row n % page_size of the page the table names
+          const int pg = min(max(P.table[(size_t)b * P.max_pages + (n >> P.page_shift)], 0), P.n_pages - 1);
+          row = (((size_t)pg * P.Hkv + j) << P.page_shift) + (n & ((1 << P.page_shift) - 1));
+        }
+        r_sh[lane] = row * D;
+        const T* kr = kb + row * D;
         float dot = 0.f;
 #pragma unroll 4
         for (int c = 0; c < D; c += VN) {
@@ -111,7 +127,7 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
       for (int i = 0; i < NC; ++i) acc[i] *= alpha;
       for (int n = 0; n < cnt; ++n) {
         const float pn = p_sh[n];
-        const T* vr = vb + (size_t)(n0 + n) * D;
+        const T* vr = vb + r_sh[n];
 #pragma unroll
         for (int i = 0; i < NC; ++i) acc[i] = fmaf(pn, Vec<T>::one(vr + lane + 64 * i), acc[i]);
       }
@@ -156,9 +172,10 @@ __global__ void __launch_bounds__(256) combine_kernel(const float* __restrict__ 
 
 }  // namespace
 
-hipError_t launch_simple(const rlda_desc& ds, hipStream_t stream) {
+hipError_t launch_simple(const Problem& ds, hipStream_t stream) {
   SimpleParams P{ds.q, ds.k_prefix, ds.v_prefix, ds.k_suffix, ds.v_suffix, ds.prefix_lens, ds.suffix_lens,
-                 ds.out, ds.lse, ds.G, ds.Hq, ds.Hkv, ds.Lp_cap, ds.Ls_cap, ds.scale};
+                 ds.out, ds.lse, ds.G, ds.Hq, ds.Hkv, ds.Lp_cap, ds.Ls_cap, ds.scale,
+                 ds.block_table, ds.page_shift, ds.max_pages, ds.n_pages, ds.seq_active};
   const int64_t blocks = (int64_t)ds.P * ds.G * ds.Hq;
   if (blocks == 0) return hipSuccess;
   const dim3 grid((unsigned)blocks), block(64);

@@ -115,3 +115,53 @@ def test_auto_selects_the_shared_prefix_path_for_bf16_d128():
     assert B.rl_decode_attn_plan(good(d=64)) == B.RLDA_ALGO_SIMPLE
     assert B.rl_decode_attn_plan(good(Hq=64, Hkv=2)) == B.RLDA_ALGO_SIMPLE          # 32 heads per KV head
     assert B.rl_decode_attn_plan(good(Hq=64, Hkv=2, algo=B.RLDA_ALGO_SHARED)) == B.RLDA_ERR_UNSUPPORTED
+
+
+# ---------------------------------------------------------------- paged descriptor
+def good_paged(**kw):
+    args = dict(dtype=B.RLDA_BF16, P=2, G=4, Hq=8, Hkv=2, d=128, Lp_cap=64, page_size=64, max_pages=4,
+                n_pages=40, scale=0.1)
+    args.update(kw)
+    return B.make_paged_desc(**args)
+
+
+def test_paged_descriptor_layout_matches_the_header():
+    # 13 four-byte fields, padding to 8, 11 pointers, pointer + size_t
+    assert ctypes.sizeof(B.rlda_paged_desc) == 56 + 11 * 8 + 16
+    assert B.rlda_paged_desc.q.offset == 56 and B.rlda_paged_desc.workspace_bytes.offset == 56 + 12 * 8
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(page_size=48), B.RLDA_ERR_UNSUPPORTED),       # not a power of two
+    (dict(page_size=16), B.RLDA_ERR_UNSUPPORTED),       # smaller than a key tile
+    (dict(page_size=0), B.RLDA_ERR_INVALID),
+    (dict(max_pages=-1), B.RLDA_ERR_INVALID),
+    (dict(n_pages=0), B.RLDA_ERR_INVALID),              # a table with columns needs a pool
+    (dict(max_pages=1 << 26, page_size=64), B.RLDA_ERR_UNSUPPORTED),
+    (dict(d=96), B.RLDA_ERR_UNSUPPORTED),
+    (dict(Hq=7), B.RLDA_ERR_UNSUPPORTED),
+])
+def test_paged_shape_errors(kw, code):
+    ds = good_paged(**kw)
+    assert B.rl_decode_attn_paged_plan(ds) == code
+    assert B.rl_decode_attn_paged_raw(ds) == code
+    assert B.rl_decode_attn_paged_workspace_bytes(ds) == 0
+
+
+def test_paged_plan_workspace_and_pointer_checks():
+    ds = good_paged()
+    assert B.rl_decode_attn_paged_plan(ds) == B.RLDA_ALGO_SHARED
+    # same partial layout as the contiguous call of the same shape
+    assert B.rl_decode_attn_paged_workspace_bytes(ds) == B.rl_decode_attn_workspace_bytes(good(Ls_cap=256))
+    assert B.rl_decode_attn_paged_plan(good_paged(dtype=B.RLDA_F32)) == B.RLDA_ALGO_SIMPLE
+    assert B.rl_decode_attn_paged_raw(ds) == B.RLDA_ERR_INVALID                 # null tensors
+    ds.struct_size = 12
+    assert B.rl_decode_attn_paged_raw(ds) == B.RLDA_ERR_STRUCT_SIZE
+    assert B._lib.rl_decode_attn_paged(None, None, None) == B.RLDA_ERR_INVALID
+    fake = 0x1000
+    ds = good_paged(q=fake, k_prefix=fake, v_prefix=fake, prefix_lens=fake, k_pages=fake, v_pages=fake,
+                    suffix_lens=fake, out=fake)
+    assert B.rl_decode_attn_paged_raw(ds) == B.RLDA_ERR_INVALID                 # block table missing
+    ds.block_table = fake
+    assert B.rl_decode_attn_paged_raw(ds) == B.RLDA_ERR_WORKSPACE               # every pointer set, no workspace
+    assert B.rl_decode_attn_paged_raw(good_paged(P=0)) == B.RLDA_OK             # empty batch: nothing to enqueue

@@ -63,3 +63,16 @@ def random_case(seed, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, dtype="bf16", plens=None
     x["prefix_lens"] = (rng.integers(0, Lp_cap + 1, P) if plens is None else np.asarray(plens)).astype(np.int32)
     x["suffix_lens"] = (rng.integers(0, Ls_cap + 1, B) if slens is None else np.asarray(slens)).astype(np.int32)
     return x
+
+
+def oracle_paged(y, scale, G, active=None, **kw):
+    from oracle import ref
+    return ref.decode_attn_paged_ref(y["q"], y["k_prefix"], y["v_prefix"], y["prefix_lens"], y["k_pages"],
+                                     y["v_pages"], y["block_table"], y["suffix_lens"], active, scale, G, **kw)
+
+
+def gpu_run_paged(t, scale, G, active=None, **kw):
+    from paper_2512_21450_amd import binding
+    return binding.rl_decode_attn_paged(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_pages"],
+                                        t["v_pages"], t["block_table"], t["suffix_lens"], scale, G,
+                                        seq_active=active, **kw)
