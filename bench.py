@@ -67,6 +67,11 @@ def main():
     ap.add_argument("--event-every", type=int, default=8, help="record per-kernel HIP events on every n-th step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="0: contiguous suffix store (the headline configuration); else rows per page of a paged store")
+    ap.add_argument("--finished", type=float, default=0.0,
+                    help="fraction of sequences marked finished (paged store only)")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -85,14 +90,27 @@ def main():
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
     x = wl.make_inputs(w, threads=16)
-    ab = wl.algorithmic_bytes(w, x["prefix_lens"], x["suffix_lens"])
+    paged = args.page_size > 0
+    active = None
+    x0 = x                                    # contiguous layout, kept for the CPU leg
+    if paged:
+        x = wl.to_pages(x, args.page_size, seed=w.seed, poison=False)
+        if args.finished > 0:
+            active = (np.random.default_rng(w.seed).random(w.B) >= args.finished).astype(np.uint8)
+    elif args.finished > 0:
+        sys.exit("bench.py: --finished needs --page-size")
+    # bytes the step must move: finished sequences contribute nothing, a prompt only if one of its sequences is live
+    live_b = np.ones(w.B, bool) if active is None else active.astype(bool)
+    live_p = live_b.reshape(w.P, w.G).any(axis=1)
+    ab = wl.algorithmic_bytes(w, np.where(live_p, x["prefix_lens"], 0), np.where(live_b, x["suffix_lens"], 0))
 
     def dev_t(a):
         if a.dtype == np.uint16:
             return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    base = {k: dev_t(v) for k, v in x.items()}
+    base = {k: dev_t(v) for k, v in x.items() if isinstance(v, np.ndarray)}
+    act_t = None if active is None else torch.from_numpy(active).to(dev)
     sets = [base] + [{k: (v.clone() if k.startswith(("k_", "v_")) else v) for k, v in base.items()}
                      for _ in range(max(args.sets, 1) - 1)]
     out = torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device=dev)
@@ -100,19 +118,25 @@ def main():
     descs = []
     ws = None
     for s in sets:
-        ds = B.desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_suffix"],
-                                 s["v_suffix"], s["suffix_lens"], w.scale, w.G, out, lse, None, algo)
+        if paged:
+            ds = B.paged_desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_pages"],
+                                           s["v_pages"], s["block_table"], s["suffix_lens"], w.scale, w.G, out, lse,
+                                           act_t, None, algo)
+        else:
+            ds = B.desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_suffix"],
+                                     s["v_suffix"], s["suffix_lens"], w.scale, w.G, out, lse, None, algo)
         if ws is None:
-            need = B.rl_decode_attn_workspace_bytes(ds)
+            need = B.rl_decode_attn_paged_workspace_bytes(ds) if paged else B.rl_decode_attn_workspace_bytes(ds)
             ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
         ds.workspace, ds.workspace_bytes = ws.data_ptr(), ws.numel()
         descs.append(ds)
-    plan = B.rl_decode_attn_plan(descs[0])
+    plan = B.rl_decode_attn_paged_plan(descs[0]) if paged else B.rl_decode_attn_plan(descs[0])
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
     def step(i, mid=None):
-        rc = B.rl_decode_attn_profiled(descs[i % len(descs)], sh, mid)
+        d_ = descs[i % len(descs)]
+        rc = B.rl_decode_attn_paged_raw(d_, sh, mid) if paged else B.rl_decode_attn_profiled(d_, sh, mid)
         if rc != 0:
             raise B.RldaError(rc)
 
@@ -148,14 +172,21 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     kern_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in timed])
     rest_ms = np.array([ev[i][1].elapsed_time(ev[i][2]) for i in timed])
-    value = w.B / (ms_per_step * 1e-3)
+    value = int(live_b.sum()) / (ms_per_step * 1e-3)    # one query token per live sequence and step
 
     # sanity: the timed configuration still matches the oracle on sampled rows
     rng = np.random.default_rng(0)
     rows = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.Hq, 64)], 1).astype(np.int32)
     from oracle import ref
-    ro, rl = ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
-                                 x["v_suffix"], x["suffix_lens"], w.scale, w.G, rows=rows)
+    def oracle(**kw):
+        if paged:
+            return ref.decode_attn_paged_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_pages"],
+                                             x["v_pages"], x["block_table"], x["suffix_lens"], active, w.scale, w.G,
+                                             **kw)
+        return ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
+                                   x["v_suffix"], x["suffix_lens"], w.scale, w.G, **kw)
+
+    ro, rl = oracle(rows=rows)
     step(0)
     torch.cuda.synchronize()
     o, l = out.cpu().numpy(), lse.cpu().numpy()
@@ -171,13 +202,18 @@ def main():
         n = min(args.cpu_seqs, w.B)
         seqs = np.linspace(0, w.B - 1, n).astype(np.int32)
         rws = np.stack([np.repeat(seqs, w.Hq), np.tile(np.arange(w.Hq, dtype=np.int32), n)], 1)
-        c0 = time.perf_counter()
-        _, _, used = ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
-                                         x["v_suffix"], x["suffix_lens"], w.scale, w.G, rows=rws,
-                                         return_threads=True)
-        c1 = time.perf_counter()
-        cpu = {"value": n / (c1 - c0), "unit": "query-tokens/s", "cores": int(used), "kind": "oracle",
-               "sample": f"{n} of {w.B} sequences (all {w.Hq} heads, evenly spaced), {c1 - c0:.2f} s"}
+        passes, c0 = 0, time.perf_counter()
+        while True:                           # whole passes over the sample until about 10 s of wall time
+            _, _, used = ref.decode_attn_ref(x0["q"], x0["k_prefix"], x0["v_prefix"], x0["prefix_lens"],
+                                             x0["k_suffix"], x0["v_suffix"], x0["suffix_lens"], w.scale, w.G,
+                                             rows=rws, return_threads=True)
+            passes += 1
+            c1 = time.perf_counter()
+            if c1 - c0 >= args.cpu_seconds:
+                break
+        cpu = {"value": passes * n / (c1 - c0), "unit": "query-tokens/s", "cores": int(used), "kind": "oracle",
+               "sample": f"{n} of {w.B} sequences (all {w.Hq} heads, evenly spaced, contiguous layout), "
+                         f"{passes} passes, {c1 - c0:.2f} s"}
 
     kern_us = float(kern_ms.mean() * 1e3)
     achieved = ab["total"] / (kern_us * 1e-6) / 1e9
@@ -188,6 +224,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.note}; suffix {w.suffix}", "P": w.P, "G": w.G, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "algo": {1: "simple", 2: "shared"}.get(plan, str(plan)),
+                   "suffix_store": f"paged, {args.page_size} rows per page" if paged else "contiguous",
+                   "finished_sequences": int((~live_b).sum()),
                    "kv_sets_rotated": len(sets),
                    "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
                    "mean_prefix_len": float(x["prefix_lens"].mean())},
@@ -195,7 +233,7 @@ def main():
         "pct_of_hbm_peak_whole_step": 100.0 * ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes": ab,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name, plan),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if paged else measured_traffic(w.name, plan),
                      "kernel": "partial_kernel" if plan == 2 else "simple_kernel",
                      "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
                      "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),
