@@ -195,3 +195,25 @@ def to_pages(x: dict, page_size: int, seed: int, spare_pages: int = 3, poison: b
     y = {k: v for k, v in x.items() if k not in ("k_suffix", "v_suffix")}
     y.update(k_pages=kp, v_pages=vp, block_table=table, page_size=page_size)
     return y
+
+
+# ---- vocabulary logits of one decode step (for the per-token policy statistics) ----------
+QWEN2_VOCAB = 151936      # vocabulary size in the public configs of the Qwen2 / Qwen2.5 (-VL) models
+
+
+def make_logits(n_rows: int, vocab: int, seed: int, dtype: str = "bf16", spread: float = 3.0,
+                with_ref: bool = False, threads: int = 8) -> dict:
+    """Seeded logits ~ spread * N(0,1) [n_rows, vocab], token ids (nine in ten uniform, one in ten
+    the row's largest logit, as sampled tokens tend to be likely ones) and, on request, reference
+    logits = logits + 0.3 * N(0,1) (a nearby policy)."""
+    lg = _normal_tensor(seed, 10, (n_rows, vocab), "f32", spread, threads)
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, vocab, n_rows).astype(np.int32)
+    top = rng.random(n_rows) < 0.1
+    ids[top] = lg[top].argmax(axis=1).astype(np.int32)
+    out = {"token_ids": ids}
+    if with_ref:
+        ref = lg + _normal_tensor(seed, 11, (n_rows, vocab), "f32", 0.3, threads)
+        out["ref_logits"] = ref if dtype == "f32" else f32_to_bf16_bits(ref)
+    out["logits"] = lg if dtype == "f32" else f32_to_bf16_bits(lg)
+    return out
