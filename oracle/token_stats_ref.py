@@ -22,8 +22,10 @@ With z = logits / T and w = ref_logits / T (both widened to fp64):
   entropy  = - sum_i p_i ln p_i             with p_i = exp(z_i - lse)
   ref_logprob = w_y - ln sum_i exp(w_i)
   kl       = sum_i p_i (ln p_i - ln r_i)    with r_i = exp(w_i - lse_w)
-Everything is written out as these definitions, in numpy fp64, one row at a
-time; nothing is fused or reordered.
+A logit of -inf (a masked token) has p_i = 0 and contributes nothing to the
+entropy and KL sums (the limit p ln p -> 0); a row must keep at least one
+finite logit.  Everything is written out as these definitions, in numpy fp64,
+one row at a time; nothing is fused or reordered.
 """
 from __future__ import annotations
 
@@ -53,7 +55,8 @@ def token_stats_ref(logits, token_ids, inv_temperature=1.0, ref_logits=None):
         logp = z - lse                              # ln p_i
         p = np.exp(logp)
         out["lse"][b] = lse
-        out["entropy"][b] = -(p * logp).sum()
+        live = p > 0
+        out["entropy"][b] = -(p[live] * logp[live]).sum()
         y = int(ids[b])
         if y >= V:
             out["logprob"][b] = np.nan
@@ -63,6 +66,6 @@ def token_stats_ref(logits, token_ids, inv_temperature=1.0, ref_logits=None):
             w = _widen(ref_logits[b]) * float(inv_temperature)
             mw = w.max()
             logr = w - (mw + np.log(np.exp(w - mw).sum()))
-            out["kl"][b] = (p * (logp - logr)).sum()
+            out["kl"][b] = (p[live] * (logp[live] - logr[live])).sum()
             out["ref_logprob"][b] = np.nan if y >= V else (logr[y] if y >= 0 else 0.0)
     return out

@@ -299,3 +299,93 @@ def rl_lse_combine(o_parts, lse_parts, out=None, lse=None, stream=None):
     if rc != RLDA_OK:
         raise RldaError(rc)
     return out, lse
+
+
+# ---------------------------------------------------------------- rl_token_logprob.h
+class rl_token_logprob_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("n_rows", ctypes.c_int64),
+        ("row_stride", ctypes.c_int64),
+        ("vocab", ctypes.c_int32),
+        ("inv_temperature", ctypes.c_float),
+        ("logits", ctypes.c_void_p), ("ref_logits", ctypes.c_void_p), ("token_ids", ctypes.c_void_p),
+        ("logprob", ctypes.c_void_p), ("lse", ctypes.c_void_p), ("entropy", ctypes.c_void_p),
+        ("ref_logprob", ctypes.c_void_p), ("kl", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+_tp = ctypes.POINTER(rl_token_logprob_desc)
+_lib.rl_token_logprob.restype = ctypes.c_int
+_lib.rl_token_logprob.argtypes = [_tp, ctypes.c_void_p]
+_lib.rl_token_logprob_workspace_bytes.restype = ctypes.c_size_t
+_lib.rl_token_logprob_workspace_bytes.argtypes = [_tp]
+
+
+def make_token_logprob_desc(dtype, n_rows, vocab, row_stride, inv_temperature=1.0, **ptrs) -> rl_token_logprob_desc:
+    ds = rl_token_logprob_desc()
+    ds.struct_size = ctypes.sizeof(rl_token_logprob_desc)
+    ds.dtype, ds.n_rows, ds.vocab, ds.row_stride, ds.inv_temperature = dtype, n_rows, vocab, row_stride, inv_temperature
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_token_logprob_workspace_bytes(desc: rl_token_logprob_desc) -> int:
+    return _lib.rl_token_logprob_workspace_bytes(ctypes.byref(desc))
+
+
+def rl_token_logprob_raw(desc: rl_token_logprob_desc, stream_handle=None) -> int:
+    return _lib.rl_token_logprob(ctypes.byref(desc), stream_handle)
+
+
+_TOKEN_OUTPUTS = ("logprob", "lse", "entropy", "ref_logprob", "kl")
+
+
+def token_logprob_desc_from_tensors(logits, token_ids, inv_temperature=1.0, ref_logits=None, outputs=None,
+                                    workspace=None) -> rl_token_logprob_desc:
+    """Descriptor over torch device tensors: logits [n_rows, vocab] (a row-strided view is fine),
+    token_ids [n_rows] int32, outputs: dict name -> fp32 tensor [n_rows]."""
+    import torch
+    if logits.dim() != 2 or logits.stride(1) != 1:
+        raise ValueError("logits must be [n_rows, vocab] with unit stride along the vocabulary")
+    if token_ids.dtype != torch.int32 or not token_ids.is_contiguous():
+        raise TypeError("token_ids must be contiguous int32")
+    code = _torch_dtype_code(logits)
+    if ref_logits is not None and (ref_logits.shape != logits.shape or ref_logits.stride() != logits.stride()
+                                   or ref_logits.dtype != logits.dtype):
+        raise ValueError("ref_logits must match logits in shape, strides and dtype")
+    n, V = logits.shape
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    outs = {k: ptr(v) for k, v in (outputs or {}).items()}
+    unknown = set(outs) - set(_TOKEN_OUTPUTS)
+    if unknown:
+        raise KeyError(f"unknown outputs {sorted(unknown)}")
+    return make_token_logprob_desc(code, n, V, logits.stride(0) if n > 1 else max(logits.stride(0), V),
+                                   float(inv_temperature), logits=ptr(logits), ref_logits=ptr(ref_logits),
+                                   token_ids=ptr(token_ids), workspace=ptr(workspace),
+                                   workspace_bytes=0 if workspace is None else workspace.numel(), **outs)
+
+
+def rl_token_logprob(logits, token_ids, inv_temperature=1.0, ref_logits=None, want=None, workspace=None,
+                     stream=None) -> dict:
+    """Per-token log-prob / lse / entropy (and ref_logprob / kl with ``ref_logits``); returns a dict of
+    fp32 device tensors [n_rows].  Asynchronous on ``stream``."""
+    import torch
+    if not logits.is_cuda:
+        raise RuntimeError("rl_token_logprob needs device tensors; there is no CPU path")
+    names = want or (_TOKEN_OUTPUTS if ref_logits is not None else _TOKEN_OUTPUTS[:3])
+    outs = {k: torch.empty(logits.shape[0], dtype=torch.float32, device=logits.device) for k in names}
+    ds = token_logprob_desc_from_tensors(logits, token_ids, inv_temperature, ref_logits, outs, workspace)
+    if workspace is None:
+        need = rl_token_logprob_workspace_bytes(ds)
+        if need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=logits.device)
+            ds.workspace, ds.workspace_bytes = workspace.data_ptr(), need
+    s = stream if stream is not None else torch.cuda.current_stream(logits.device)
+    rc = _lib.rl_token_logprob(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return outs

@@ -165,3 +165,39 @@ def test_paged_plan_workspace_and_pointer_checks():
     ds.block_table = fake
     assert B.rl_decode_attn_paged_raw(ds) == B.RLDA_ERR_WORKSPACE               # every pointer set, no workspace
     assert B.rl_decode_attn_paged_raw(good_paged(P=0)) == B.RLDA_OK             # empty batch: nothing to enqueue
+
+
+# ---------------------------------------------------------------- rl_token_logprob
+def good_tl(**kw):
+    args = dict(dtype=B.RLDA_BF16, n_rows=8, vocab=1000, row_stride=1000)
+    args.update(kw)
+    return B.make_token_logprob_desc(**args)
+
+
+def test_token_logprob_descriptor_layout():
+    assert ctypes.sizeof(B.rl_token_logprob_desc) == 32 + 9 * 8 + 8
+    assert B.rl_token_logprob_desc.logits.offset == 32
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(dtype=3), -2), (dict(row_stride=1004), -2), (dict(row_stride=992), -2), (dict(vocab=0), -1),
+    (dict(n_rows=-1), -1), (dict(dtype=B.RLDA_F32, row_stride=1002), -2), (dict(n_rows=1 << 40), -2),
+])
+def test_token_logprob_shape_errors(kw, code):
+    ds = good_tl(**kw)
+    assert B.rl_token_logprob_raw(ds) == code
+    assert B.rl_token_logprob_workspace_bytes(ds) == 0
+
+
+def test_token_logprob_pointer_and_workspace_checks():
+    assert B.rl_token_logprob_raw(good_tl(n_rows=0)) == 0
+    assert B.rl_token_logprob_raw(good_tl()) == -1                           # logits missing
+    fake = 0x1000
+    assert B.rl_token_logprob_raw(good_tl(logits=fake, token_ids=fake, kl=fake)) == -1   # kl without reference
+    assert B.rl_token_logprob_raw(good_tl(logits=fake + 4, token_ids=fake)) == -2        # misaligned rows
+    big = good_tl(vocab=152000, row_stride=152000, logits=fake, token_ids=fake)
+    assert B.rl_token_logprob_workspace_bytes(big) == 8 * 18 * 6 * 4                     # 18 splits of >= 8192 logits
+    assert B.rl_token_logprob_raw(big) == -3
+    ds = good_tl(); ds.struct_size = 4
+    assert B.rl_token_logprob_raw(ds) == -4
+    assert B._lib.rl_token_logprob(None, None) == -1

@@ -1,0 +1,111 @@
+"""GPU parity of rl_token_logprob against the fp64 oracle, through the C ABI.
+
+Tolerances (absolute): 2e-5 on logprob, lse, ref_logprob; 1e-4 on entropy and kl.  The kernel
+works in fp32: every output is a sum of at most four terms of magnitude <= 32 (lse, the
+probability-weighted mean logits), each carried to about 2^-20 relative after a 150k-term
+reduction, i.e. ~1e-5 absolute per term.
+"""
+import numpy as np
+import pytest
+
+from oracle.token_stats_ref import token_stats_ref
+from paper_2512_21450_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+TOL = {"logprob": 2e-5, "lse": 2e-5, "ref_logprob": 2e-5, "entropy": 1e-4, "kl": 1e-4}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2512_21450_amd import binding
+    return binding
+
+
+def dev(a):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def check(B, x, invT=1.0, what="", stride=None):
+    import torch
+    lg, rf = dev(x["logits"]), (dev(x["ref_logits"]) if "ref_logits" in x else None)
+    if stride is not None:                       # rows embedded in a wider buffer
+        n, V = lg.shape
+        wide = torch.full((n, stride), 77.0, dtype=lg.dtype, device="cuda"); wide[:, :V] = lg; lg = wide[:, :V]
+        if rf is not None:
+            wr = torch.full((n, stride), -55.0, dtype=rf.dtype, device="cuda"); wr[:, :V] = rf; rf = wr[:, :V]
+    got = B.rl_token_logprob(lg, dev(x["token_ids"]), invT, rf)
+    torch.cuda.synchronize()
+    ref = token_stats_ref(x["logits"], x["token_ids"], invT, x.get("ref_logits"))
+    for k, r in ref.items():
+        g = got[k].cpu().numpy().astype(np.float64)
+        same_nan = np.array_equal(np.isnan(g), np.isnan(r))
+        same_inf = np.array_equal(np.isinf(g), np.isinf(r)) and np.array_equal(g[np.isinf(r)], r[np.isinf(r)])
+        assert same_nan and same_inf, f"{what}: {k}: NaN/inf pattern differs"
+        fin = np.isfinite(r)
+        err = np.abs(g[fin] - r[fin]).max() if fin.any() else 0.0
+        assert err <= TOL[k], f"{what}: {k}: max abs err {err:.3e} > {TOL[k]}"
+    return got
+
+
+def test_full_size_decode_step_bf16_with_reference(B):
+    x = wl.make_logits(256, wl.QWEN2_VOCAB, seed=2001, dtype="bf16", with_ref=True, threads=8)
+    print("logits", x["logits"].shape, flush=True)
+    check(B, x, what="256 x 151936 bf16 + ref")
+
+
+@pytest.mark.parametrize("n,V,dtype,ref", [
+    (1, 1, "f32", False), (3, 5, "bf16", True), (7, 1001, "f32", True), (7, 1001, "bf16", True),
+    (64, 32000, "bf16", False), (33, 65537, "f32", True), (5, 151936, "f32", True),
+    (2100, 4099, "bf16", True),               # one split per row: the streaming kernel writes the results itself
+    (4096, 8192, "f32", False),
+])
+def test_shapes_dtypes_and_split_counts(B, n, V, dtype, ref):
+    vn = 4 if dtype == "f32" else 8
+    stride = (V + vn - 1) // vn * vn + (vn if n % 2 else 0)
+    x = wl.make_logits(n, V, seed=100 + n, dtype=dtype, with_ref=ref)
+    check(B, x, what=f"{n}x{V} {dtype}", stride=stride)
+
+
+@pytest.mark.parametrize("invT", [0.25, 1.0, 1.0 / 0.7])
+def test_temperature(B, invT):
+    x = wl.make_logits(40, 50000, seed=7, dtype="bf16", with_ref=True)
+    check(B, x, invT, what=f"invT {invT}")
+
+
+def test_ignored_and_out_of_range_ids_and_masked_logits(B):
+    x = wl.make_logits(12, 20011, seed=9, dtype="f32", with_ref=True)
+    x["token_ids"][[0, 5]] = [-100, -1]
+    x["token_ids"][[1, 6]] = [20011, 2_000_000_000]
+    x["logits"][:, 100:9000] = -np.inf                       # masked tokens, whole vectors and whole chunks of them
+    x["logits"][3, :] = -np.inf; x["logits"][3, 20010] = 2.5   # a single live logit at the very end
+    x["token_ids"][4] = 150                                  # a masked token was "sampled": log-prob -inf
+    x["ref_logits"][2, 100:9000] = -np.inf                   # reference masked alike on row 2: finite KL there
+    got = check(B, x, what="ids and masks", stride=20012)
+    assert got["logprob"][0] == 0 and got["logprob"][5] == 0 and got["ref_logprob"][0] == 0
+
+
+def test_peaked_and_large_logits(B):
+    lg = np.full((4, 30000), -30.0, np.float32)
+    lg[0, 123] = 80.0; lg[1, 29999] = 50.0; lg[2, :] = 100.0; lg[3, 0] = -100.0
+    x = {"logits": lg, "token_ids": np.array([123, 0, 7, 0], np.int32), "ref_logits": lg[::-1].copy()}
+    check(B, x, what="peaked")
+
+
+def test_repeatable_and_outputs_optional(B):
+    import torch
+    x = wl.make_logits(100, 40000, seed=5, dtype="bf16", with_ref=True)
+    lg, rf, ids = dev(x["logits"]), dev(x["ref_logits"]), dev(x["token_ids"])
+    a = B.rl_token_logprob(lg, ids, 1.0, rf)
+    b = B.rl_token_logprob(lg, ids, 1.0, rf)
+    only = B.rl_token_logprob(lg, ids, 1.0, rf, want=("kl",))
+    torch.cuda.synchronize()
+    for k in a:
+        assert torch.equal(a[k], b[k]), k
+    assert torch.equal(only["kl"], a["kl"]) and set(only) == {"kl"}
+    plain = B.rl_token_logprob(lg, ids)
+    assert torch.equal(plain["logprob"], a["logprob"]) and set(plain) == {"logprob", "lse", "entropy"}

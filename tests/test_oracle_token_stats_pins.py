@@ -146,3 +146,22 @@ def test_generator_is_seeded_and_ids_in_range():
     assert all(np.array_equal(a[k], b[k]) for k in a)
     assert a["logits"].dtype == np.uint16 and a["token_ids"].dtype == np.int32
     assert (a["token_ids"] >= 0).all() and (a["token_ids"] < 1000).all()
+
+
+def test_masked_logits_are_the_distribution_over_the_rest():
+    rng = np.random.default_rng(12)
+    lg = rng.standard_normal((2, 40)).astype(np.float32)
+    rf = rng.standard_normal((2, 40)).astype(np.float32)
+    keep = np.ones(40, bool); keep[[3, 17, 18, 39]] = False
+    m, mr = lg.copy(), rf.copy()
+    m[:, ~keep] = -np.inf
+    ids_full = np.array([5, 20])
+    ids_kept = np.array([int(keep[:5].sum()), int(keep[:20].sum())])
+    a = token_stats_ref(m, ids_full, ref_logits=rf)
+    b = token_stats_ref(lg[:, keep], ids_kept, ref_logits=rf[:, keep])
+    assert np.allclose(a["logprob"], b["logprob"], atol=1e-13) and np.allclose(a["entropy"], b["entropy"], atol=1e-13)
+    # KL against a reference that keeps its mass on the masked tokens differs; against one masked alike it matches
+    mr[:, ~keep] = -np.inf
+    c = token_stats_ref(m, ids_full, ref_logits=mr)
+    assert np.allclose(c["kl"], b["kl"], atol=1e-13) and np.allclose(c["ref_logprob"], b["ref_logprob"], atol=1e-13)
+    assert np.isneginf(token_stats_ref(m, [3, 3])["logprob"]).all()
