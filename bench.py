@@ -73,6 +73,11 @@ def main():
                     help="fraction of sequences marked finished (paged store only)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob"],
+                    help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel")
+    ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
+    ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
+    ap.add_argument("--no-ref", action="store_true", help="token_logprob: no reference logits (no KL)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is a single-GPU kernel library; only --gpus 1 is supported "
@@ -86,6 +91,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.op == "token_logprob":
+        return bench_token_logprob(args, torch, B, wl, dev)
     w = wl.WORKLOADS[args.workload]
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
@@ -243,6 +250,76 @@ def main():
     }
     print(json.dumps(res))
     if not parity_ok:
+        sys.exit(1)
+
+
+def bench_token_logprob(args, torch, B, wl, dev):
+    """One step = one rl_token_logprob call over [rows, vocab] bf16 logits (+ reference logits)."""
+    V = args.vocab or wl.QWEN2_VOCAB
+    n, ref = args.rows, not args.no_ref
+    x = wl.make_logits(n, V, seed=3001, dtype="bf16", with_ref=ref, threads=16)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    ids = torch.from_numpy(x["token_ids"]).to(dev)
+    sets = [(to_dev(x["logits"]), to_dev(x["ref_logits"]) if ref else None)]
+    for _ in range(max(args.sets, 1) - 1):
+        sets.append(tuple(None if t is None else t.clone() for t in sets[0]))
+    names = ("logprob", "lse", "entropy", "ref_logprob", "kl") if ref else ("logprob", "lse", "entropy")
+    outs = {k: torch.empty(n, dtype=torch.float32, device=dev) for k in names}
+    descs, ws = [], None
+    for lg, rf in sets:
+        ds = B.token_logprob_desc_from_tensors(lg, ids, 1.0, rf, outs)
+        if ws is None:
+            ws = torch.empty(max(B.rl_token_logprob_workspace_bytes(ds), 256), dtype=torch.uint8, device=dev)
+        ds.workspace, ds.workspace_bytes = ws.data_ptr(), ws.numel()
+        descs.append(ds)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        rc = B.rl_token_logprob_raw(descs[i % len(descs)], stream.cuda_stream)
+        if rc != 0:
+            raise B.RldaError(rc)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    every = max(args.event_every, 1)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        if i % every == 0:
+            ev[i][0].record(stream); step(i); ev[i][1].record(stream)
+        else:
+            step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    call_us = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for i in range(0, args.steps, every)]) * 1e3)
+    nbytes = n * V * 2 * (2 if ref else 1) + n * 4 * (1 + len(names))
+
+    from oracle.token_stats_ref import token_stats_ref
+    rows = np.linspace(0, n - 1, min(n, 16)).astype(np.int64)
+    c0 = time.perf_counter()
+    r = token_stats_ref(x["logits"][rows], x["token_ids"][rows], 1.0, x["ref_logits"][rows] if ref else None)
+    c1 = time.perf_counter()
+    tol = {"logprob": 2e-5, "lse": 2e-5, "ref_logprob": 2e-5, "entropy": 1e-4, "kl": 1e-4}
+    errs = {k: float(np.abs(outs[k].cpu().numpy()[rows] - r[k]).max()) for k in names}
+    ok = all(errs[k] <= tol[k] for k in names)
+    achieved = nbytes / (call_us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "token log-prob / entropy / KL rows per second and achieved HBM GB/s", "value": n / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"token_logprob: {n} rows x {V} bf16 logits" + (" + reference logits" if ref else ""),
+                   "kv_sets_rotated": len(sets)},
+        "algorithmic_bytes": nbytes,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "token_partial_kernel (+ final merge)",
+                     "call_us_mean": call_us},
+        "cpu_baseline": {"value": len(rows) / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                         "sample": f"{len(rows)} of {n} rows, {c1 - c0:.2f} s"},
+        "parity": {"ok": ok, "max_abs_err": errs},
+    }))
+    if not ok:
         sys.exit(1)
 
 

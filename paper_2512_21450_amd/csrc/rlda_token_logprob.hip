@@ -11,6 +11,12 @@
 // splits (second kernel, one wavefront per row).  Then
 //   lse = m + ln s, entropy = lse - t/s, kl = (t - u)/s - lse + (mr + ln sr).
 // All merges have a fixed order, so results do not change from call to call.
+//
+// The inner loop is close to the vector-ALU limit at HBM speed (bf16: ~12 issue slots per
+// logit are available at 6.5 TB/s, the exponential alone takes 4), so the state is kept in
+// base 2 (a, b pre-multiplied by inv_temperature * log2 e: the hardware exponential is 2^x) and
+// masked logits (-inf) are clamped to -1e30, which makes 0 * a finite without a branch and
+// cannot overflow a sum.
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -19,7 +25,8 @@
 
 namespace {
 
-constexpr int NT = 256;            // threads per workgroup
+// threads per workgroup: 256 when there are thousands of workgroups, 1024 when there is about one
+// per compute unit (a decode step's few hundred rows), so that either way the chip is full
 constexpr int UNR = 4;             // independent 16-byte loads in flight per thread
 constexpr int MAX_SPLITS = 64;     // one lane per split in the final merge
 
@@ -31,15 +38,18 @@ struct Params {
   float* part;                     // [n_rows][S][6]
   long long stride;                // elements
   int V, S, chunk;                 // chunk: elements per split, multiple of the vector width
-  float invT;
+  float k2;                        // inv_temperature * log2(e): logits -> base-2 exponents
 };
+
+constexpr float LN2 = 0.69314718055994531f;
+constexpr float MASKED = -1e30f;        // stands for a logit of -inf inside the reductions
 
 struct Acc { float m, s, t, mr, sr, u; };
 
 __device__ __forceinline__ Acc acc_empty() { return Acc{-INFINITY, 0.f, 0.f, -INFINITY, 0.f, 0.f}; }
 
-__device__ __forceinline__ float rescale(float m_old, float m_new) {      // e^(m_old - m_new), 0 for an empty side
-  return m_old == -INFINITY ? 0.f : __expf(m_old - m_new);
+__device__ __forceinline__ float rescale(float m_old, float m_new) {      // 2^(m_old - m_new), 0 for an empty side
+  return m_old == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_old - m_new);
 }
 
 template <bool REF>
@@ -90,7 +100,9 @@ template <> struct Elem<uint16_t> {
   }
 };
 
-// N values of the row (and of the reference row) into the thread's state
+// N values of the row (and of the reference row), already in base-2 units and >= MASKED, into the
+// thread's state.  Next to a live logit a masked one gives e = 2^(MASKED - m) = 0 and adds 0 * MASKED = 0; a state
+// that has seen masked logits only (m = MASKED) is wiped by the rescale when the first live one arrives.
 template <bool REF, int N>
 __device__ __forceinline__ void absorb(Acc& A, const float (&a)[N], const float (&b)[N]) {
   float cm = a[0];
@@ -98,16 +110,13 @@ __device__ __forceinline__ void absorb(Acc& A, const float (&a)[N], const float 
   for (int i = 1; i < N; ++i) cm = fmaxf(cm, a[i]);
   const float mn = fmaxf(A.m, cm);
   const float c = rescale(A.m, mn);
-  const float ms = mn == -INFINITY ? 0.f : mn;              // only masked (-inf) logits so far: every e is 0
   float s = A.s * c, t = A.t * c, u = A.u * c;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    const float e = __expf(a[i] - ms);
+    const float e = __builtin_amdgcn_exp2f(a[i] - mn);
     s += e;
-    if (e > 0.f) {                                          // a masked logit has p = 0 and adds nothing (0 * -inf)
-      t = fmaf(e, a[i], t);
-      if (REF) u = fmaf(e, b[i], u);
-    }
+    t = fmaf(e, a[i], t);
+    if (REF) u = fmaf(e, b[i], u);
   }
   A.m = mn; A.s = s; A.t = t; A.u = u;
   if (REF) {
@@ -115,30 +124,35 @@ __device__ __forceinline__ void absorb(Acc& A, const float (&a)[N], const float 
 #pragma unroll
     for (int i = 1; i < N; ++i) cr = fmaxf(cr, b[i]);
     const float mrn = fmaxf(A.mr, cr);
-    const float mrs = mrn == -INFINITY ? 0.f : mrn;
     float sr = A.sr * rescale(A.mr, mrn);
 #pragma unroll
-    for (int i = 0; i < N; ++i) sr += __expf(b[i] - mrs);
+    for (int i = 0; i < N; ++i) sr += __builtin_amdgcn_exp2f(b[i] - mrn);
     A.mr = mrn; A.sr = sr;
   }
 }
 
+// State (base-2 units) -> outputs (natural units).  a_y, b_y: the sampled token's scaled logits.
 template <bool REF>
 __device__ __forceinline__ void finish_row(const Params& P, long long row, const Acc& A, float a_y, float b_y, int y) {
-  const float lse = A.m + logf(A.s);
-  const float mean_a = A.t / A.s;                          // sum_i p_i a_i
+  const bool dead = A.m <= MASKED;                           // every logit masked: no distribution
+  const float lse2 = A.m + __log2f(A.s);
+  const float mean_a = A.t / A.s;                           // sum_i p_i a_i
+  const float lse = dead ? -INFINITY : lse2 * LN2;
   if (P.lse) P.lse[row] = lse;
-  if (P.entropy) P.entropy[row] = lse - mean_a;
-  if (P.logprob) P.logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : a_y - lse);
+  if (P.entropy) P.entropy[row] = dead ? NAN : (lse2 - mean_a) * LN2;
+  if (P.logprob) P.logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (a_y <= MASKED ? -INFINITY : (a_y - lse2) * LN2));
   if (REF) {
-    const float lse_r = A.mr + logf(A.sr);
-    if (P.kl) P.kl[row] = mean_a - A.u / A.s - lse + lse_r;
-    if (P.ref_logprob) P.ref_logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : b_y - lse_r);
+    const float lse_r2 = A.mr + __log2f(A.sr);
+    float mean_b = A.u / A.s;                               // sum_i p_i b_i; a masked reference logit under p > 0
+    if (mean_b < -1e6f) mean_b = -INFINITY;                 // drags it towards MASKED: the KL is infinite
+    if (P.kl) P.kl[row] = dead ? NAN : (mean_a - mean_b - lse2 + lse_r2) * LN2;
+    if (P.ref_logprob)
+      P.ref_logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (b_y <= MASKED ? -INFINITY : (b_y - lse_r2) * LN2));
   }
 }
 
 // workgroup row * S + split: partial state of elements [split * chunk, min(V, (split + 1) * chunk)) of a row
-template <typename T, bool REF>
+template <typename T, bool REF, int NT>
 __global__ void __launch_bounds__(NT) token_partial_kernel(const Params P) {
   constexpr int VN = Elem<T>::VN;
   __shared__ Acc red[NT / 64];
@@ -165,7 +179,10 @@ __global__ void __launch_bounds__(NT) token_partial_kernel(const Params P) {
         Elem<T>::unpack(ra[k], a);
         if (REF) Elem<T>::unpack(rb[k], b);
 #pragma unroll
-        for (int i = 0; i < VN; ++i) { a[i] *= P.invT; b[i] = REF ? b[i] * P.invT : 0.f; }
+        for (int i = 0; i < VN; ++i) {
+          a[i] = fmaxf(a[i] * P.k2, MASKED);
+          b[i] = REF ? fmaxf(b[i] * P.k2, MASKED) : 0.f;
+        }
         absorb<REF, VN>(A, a, b);
       }
     }
@@ -173,8 +190,8 @@ __global__ void __launch_bounds__(NT) token_partial_kernel(const Params P) {
   // the row's last V % VN elements, one per thread, belong to the split that holds them
   const int tail0 = v1 * VN;
   if (c1 == P.V && c1 > c0 && tail0 + tid < c1) {
-    float a[1] = {Elem<T>::one(za, tail0 + tid) * P.invT};
-    float b[1] = {REF ? Elem<T>::one(zb, tail0 + tid) * P.invT : 0.f};
+    float a[1] = {fmaxf(Elem<T>::one(za, tail0 + tid) * P.k2, MASKED)};
+    float b[1] = {REF ? fmaxf(Elem<T>::one(zb, tail0 + tid) * P.k2, MASKED) : 0.f};
     absorb<REF, 1>(A, a, b);
   }
 #pragma unroll
@@ -188,8 +205,8 @@ __global__ void __launch_bounds__(NT) token_partial_kernel(const Params P) {
     if (P.S == 1) {
       const int y = P.ids[row];
       const bool ok = y >= 0 && y < P.V;
-      finish_row<REF>(P, row, R, ok ? Elem<T>::one(za, y) * P.invT : 0.f,
-                      REF && ok ? Elem<T>::one(zb, y) * P.invT : 0.f, y);
+      finish_row<REF>(P, row, R, ok ? Elem<T>::one(za, y) * P.k2 : 0.f,
+                      REF && ok ? Elem<T>::one(zb, y) * P.k2 : 0.f, y);
     } else {
       float* o = P.part + ((size_t)row * P.S + split) * 6;
       o[0] = R.m; o[1] = R.s; o[2] = R.t; o[3] = R.mr; o[4] = R.sr; o[5] = R.u;
@@ -214,8 +231,8 @@ __global__ void __launch_bounds__(64) token_final_kernel(const Params P) {
     const char* zb = REF ? P.ref + (size_t)row * P.stride * sizeof(T) : nullptr;
     const int y = P.ids[row];
     const bool ok = y >= 0 && y < P.V;
-    finish_row<REF>(P, row, A, ok ? Elem<T>::one(za, y) * P.invT : 0.f,
-                    REF && ok ? Elem<T>::one(zb, y) * P.invT : 0.f, y);
+    finish_row<REF>(P, row, A, ok ? Elem<T>::one(za, y) * P.k2 : 0.f,
+                    REF && ok ? Elem<T>::one(zb, y) * P.k2 : 0.f, y);
   }
 }
 
@@ -231,10 +248,13 @@ int check(const rl_token_logprob_desc* d) {
   return 0;
 }
 
+// Splits per row.  From about one row per compute unit upwards a row is not split (one kernel, no
+// merge pass, which costs more than a slightly uneven last wave of workgroups); fewer rows are
+// split until there is a workgroup per compute unit, but never below 8192 logits per workgroup.
 int splits_for(const rl_token_logprob_desc* d) {
-  if (d->n_rows <= 0) return 1;
-  long long s = (2048 + d->n_rows - 1) / d->n_rows;        // enough workgroups to fill 256 compute units
-  const long long by_size = d->vocab / 8192;               // but at least 8192 logits per workgroup
+  if (d->n_rows <= 0 || d->n_rows >= 192) return 1;
+  long long s = (256 + d->n_rows - 1) / d->n_rows;
+  const long long by_size = d->vocab / 8192;
   if (s > by_size) s = by_size;
   if (s > MAX_SPLITS) s = MAX_SPLITS;
   return s < 1 ? 1 : (int)s;
@@ -272,14 +292,20 @@ int rl_token_logprob(const rl_token_logprob_desc* d, void* hip_stream) {
   P.stride = d->row_stride; P.V = d->vocab; P.S = S;
   const int per = (d->vocab + S - 1) / S;
   P.chunk = (per + vn - 1) / vn * vn;
-  P.invT = d->inv_temperature;
+  P.k2 = d->inv_temperature * 1.4426950408889634f;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const dim3 grid((unsigned)(d->n_rows * S)), fin((unsigned)d->n_rows);
   const bool ref = d->ref_logits != nullptr;
+  const bool wide = d->n_rows * S <= 512;                  // few workgroups: make each one 16 wavefronts
 #define RLTL_LAUNCH(T)                                                                                      \
   do {                                                                                                      \
-    if (ref) hipLaunchKernelGGL((token_partial_kernel<T, true>), grid, dim3(NT), 0, st, P);                 \
-    else     hipLaunchKernelGGL((token_partial_kernel<T, false>), grid, dim3(NT), 0, st, P);                \
+    if (wide) {                                                                                             \
+      if (ref) hipLaunchKernelGGL((token_partial_kernel<T, true, 1024>), grid, dim3(1024), 0, st, P);       \
+      else     hipLaunchKernelGGL((token_partial_kernel<T, false, 1024>), grid, dim3(1024), 0, st, P);      \
+    } else {                                                                                                \
+      if (ref) hipLaunchKernelGGL((token_partial_kernel<T, true, 256>), grid, dim3(256), 0, st, P);         \
+      else     hipLaunchKernelGGL((token_partial_kernel<T, false, 256>), grid, dim3(256), 0, st, P);        \
+    }                                                                                                       \
     if (S > 1) {                                                                                            \
       if (ref) hipLaunchKernelGGL((token_final_kernel<T, true>), fin, dim3(64), 0, st, P);                  \
       else     hipLaunchKernelGGL((token_final_kernel<T, false>), fin, dim3(64), 0, st, P);                 \

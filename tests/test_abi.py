@@ -196,7 +196,8 @@ def test_token_logprob_pointer_and_workspace_checks():
     assert B.rl_token_logprob_raw(good_tl(logits=fake, token_ids=fake, kl=fake)) == -1   # kl without reference
     assert B.rl_token_logprob_raw(good_tl(logits=fake + 4, token_ids=fake)) == -2        # misaligned rows
     big = good_tl(vocab=152000, row_stride=152000, logits=fake, token_ids=fake)
-    assert B.rl_token_logprob_workspace_bytes(big) == 8 * 18 * 6 * 4                     # 18 splits of >= 8192 logits
+    assert B.rl_token_logprob_workspace_bytes(big) == 8 * 18 * 6 * 4                     # 18 splits of >= 8192 logits each
+    assert B.rl_token_logprob_workspace_bytes(good_tl(n_rows=200, vocab=152000, row_stride=152000)) == 0   # unsplit
     assert B.rl_token_logprob_raw(big) == -3
     ds = good_tl(); ds.struct_size = 4
     assert B.rl_token_logprob_raw(ds) == -4
