@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "ab6423e9612181d67bd76a0fb4907a28ea492f4a8430b76553d74d8e9a1ed44a",
-    "fetch_bytes": 623887028,
-    "write_bytes": 18228224,
+    "csrc_sha256": "972a3b49ffdb79ed085b39ae0a291abe5718b3198219f8c978290781a417cc5e",
+    "fetch_bytes": 623879017,
+    "write_bytes": 18228531,
 }
 
 
