@@ -98,8 +98,9 @@ typedef struct {
  * device, so out-of-range values cannot be rejected here; the kernels clamp
  * them to [0, cap].  Rows at or beyond a length are never used and may hold
  * anything (including NaN).  Returns RLDA_OK or a negative RLDA_ERR_* code; on
- * error nothing has been enqueued.  Results are bit-reproducible from call to
- * call for identical inputs.
+ * a validation error (-1 .. -4) nothing has been enqueued; after RLDA_ERR_LAUNCH
+ * part of the work may have been, and out / lse are then undefined.  Results
+ * are bit-reproducible from call to call for identical inputs.
  */
 int rl_decode_attn(const rlda_desc* desc, void* hip_stream);
 

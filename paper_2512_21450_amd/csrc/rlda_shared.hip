@@ -23,6 +23,8 @@
 #include "rlda_internal.h"
 #include "rlda_sched.h"
 
+#include <mutex>
+
 namespace rlda {
 namespace {
 
@@ -698,15 +700,22 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
       {partial_kernel<1, 1, false>, partial_kernel<2, 1, false>, partial_kernel<4, 1, false>, partial_kernel<4, 2, false>},
       {partial_kernel<1, 1, true>, partial_kernel<2, 1, true>, partial_kernel<4, 1, true>, partial_kernel<4, 2, true>}};
   const kern_t kern = kerns[ext][nt == 2 ? 3 : nrb == 1 ? 0 : nrb == 2 ? 1 : 2];
-  static bool attr_set = false;                             // more than 64 KB of LDS in total needs an opt-in
-  if (!attr_set) {
-    for (int i = 0; i < 8; ++i) {
-      const kern_t f = kerns[i / 4][i % 4];
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(f),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-      if (e != hipSuccess) return e;
+  // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
+  {
+    static std::mutex mu;
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64 || !done[dev]) {
+      for (int i = 0; i < 8; ++i) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i / 4][i % 4]),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+      }
+      if (dev >= 0 && dev < 64) done[dev] = true;
     }
-    attr_set = true;
   }
   hipLaunchKernelGGL(kern, dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
