@@ -217,3 +217,32 @@ def make_logits(n_rows: int, vocab: int, seed: int, dtype: str = "bf16", spread:
         out["ref_logits"] = ref if dtype == "f32" else f32_to_bf16_bits(ref)
     out["logits"] = lg if dtype == "f32" else f32_to_bf16_bits(lg)
     return out
+
+
+# ---- rotary embedding inputs of a decode step ----------------------------------------------
+def rope_inv_freq(d: int, base: float = 1.0e6) -> np.ndarray:
+    """inv_freq[i] = base^(-2i/d), i < d/2, as fp32 (base 1e6 as in the public Qwen2-VL configs)."""
+    return (1.0 / (base ** (np.arange(0, d, 2, dtype=np.float64) / d))).astype(np.float32)
+
+
+def mrope_sections(d: int) -> tuple:
+    """Frequency indices per (temporal, height, width) component: 16/24/24 at d = 128, scaled otherwise."""
+    half = d // 2
+    t = half // 4
+    h = (half - t) // 2
+    return (t, h, half - t - h)
+
+
+def make_new_token(w: Workload, x: dict, seed: int) -> dict:
+    """The projections of one new token per sequence (q, k_new, v_new ~ N(0,1)) and its three position
+    components: text tokens (all equal: prompt length + suffix length) for most sequences, and for
+    every fifth sequence an image-patch-like triple (different height / width indices)."""
+    t = lambda i, shape: _normal_tensor(seed, i, shape, w.dtype, 1.0, 1)
+    pos = (np.repeat(np.asarray(x["prefix_lens"]), w.G) + np.asarray(x["suffix_lens"])).astype(np.int32)
+    p3 = np.stack([pos, pos, pos]).astype(np.int32)
+    rng = np.random.default_rng(seed)
+    img = np.arange(w.B) % 5 == 4
+    p3[1, img] = rng.integers(0, 48, int(img.sum()))
+    p3[2, img] = rng.integers(0, 48, int(img.sum()))
+    return {"q": t(20, (w.B, w.Hq, w.d)), "k_new": t(21, (w.B, w.Hkv, w.d)), "v_new": t(22, (w.B, w.Hkv, w.d)),
+            "positions": p3, "inv_freq": rope_inv_freq(w.d), "sections": mrope_sections(w.d)}
