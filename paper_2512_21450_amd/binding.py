@@ -389,3 +389,83 @@ def rl_token_logprob(logits, token_ids, inv_temperature=1.0, ref_logits=None, wa
     if rc != RLDA_OK:
         raise RldaError(rc)
     return outs
+
+
+# ---------------------------------------------------------------- rl_kv_append.h
+class rl_kv_append_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("B", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("Ls_cap", ctypes.c_int32),
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32), ("n_pages", ctypes.c_int32),
+        ("sections", ctypes.c_int32 * 3),
+        ("q", ctypes.c_void_p), ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
+        ("positions", ctypes.c_void_p), ("inv_freq", ctypes.c_void_p),
+        ("k_store", ctypes.c_void_p), ("v_store", ctypes.c_void_p),
+        ("block_table", ctypes.c_void_p), ("suffix_lens", ctypes.c_void_p), ("seq_active", ctypes.c_void_p),
+    ]
+
+
+_lib.rl_kv_append_rope.restype = ctypes.c_int
+_lib.rl_kv_append_rope.argtypes = [ctypes.POINTER(rl_kv_append_desc), ctypes.c_void_p]
+
+
+def make_kv_append_desc(dtype, B, Hq, Hkv, d, sections, Ls_cap=0, page_size=0, max_pages=0, n_pages=0,
+                        **ptrs) -> rl_kv_append_desc:
+    ds = rl_kv_append_desc()
+    ds.struct_size = ctypes.sizeof(rl_kv_append_desc)
+    ds.dtype, ds.B, ds.Hq, ds.Hkv, ds.d, ds.Ls_cap = dtype, B, Hq, Hkv, d, Ls_cap
+    ds.page_size, ds.max_pages, ds.n_pages = page_size, max_pages, n_pages
+    ds.sections[:] = list(sections)
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_kv_append_rope_raw(desc: rl_kv_append_desc, stream_handle=None) -> int:
+    return _lib.rl_kv_append_rope(ctypes.byref(desc), stream_handle)
+
+
+def kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
+                                block_table=None, seq_active=None) -> rl_kv_append_desc:
+    """Descriptor over torch device tensors.  ``k_store`` / ``v_store`` are [B, Hkv, Ls_cap, d], or with
+    ``block_table`` the page pools [n_pages, Hkv, page_size, d]."""
+    import torch
+    B, Hq, d = q.shape
+    Hkv = k_new.shape[1]
+    code = _torch_dtype_code(q)
+    for t in (k_new, v_new, k_store, v_store):
+        if _torch_dtype_code(t) != code:
+            raise TypeError("q, k_new, v_new and the stores must share one element type")
+    if positions.dtype != torch.int32 or tuple(positions.shape) != (3, B) or inv_freq.dtype != torch.float32:
+        raise TypeError("positions must be int32 [3, B] and inv_freq float32 [d/2]")
+    if suffix_lens.dtype != torch.int32 or (block_table is not None and block_table.dtype != torch.int32):
+        raise TypeError("suffix_lens / block_table must be int32")
+    for t in (q, k_new, v_new, positions, inv_freq, k_store, v_store, suffix_lens):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    kw = dict(q=ptr(q), k_new=ptr(k_new), v_new=ptr(v_new), positions=ptr(positions), inv_freq=ptr(inv_freq),
+              k_store=ptr(k_store), v_store=ptr(v_store), block_table=ptr(block_table),
+              suffix_lens=ptr(suffix_lens), seq_active=ptr(seq_active))
+    if block_table is None:
+        if tuple(k_store.shape[:2]) != (B, Hkv):
+            raise ValueError("contiguous store must be [B, Hkv, Ls_cap, d]")
+        return make_kv_append_desc(code, B, Hq, Hkv, d, sections, Ls_cap=k_store.shape[2], **kw)
+    return make_kv_append_desc(code, B, Hq, Hkv, d, sections, page_size=k_store.shape[2],
+                               max_pages=block_table.shape[1], n_pages=k_store.shape[0], **kw)
+
+
+def rl_kv_append_rope(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
+                      block_table=None, seq_active=None, stream=None) -> None:
+    """Rotate q (in place) and k_new, append k / v to the store, increment suffix_lens.  Asynchronous."""
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_kv_append_rope needs device tensors; there is no CPU path")
+    ds = kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
+                                     block_table, seq_active)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_kv_append_rope(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)

@@ -202,3 +202,27 @@ def test_token_logprob_pointer_and_workspace_checks():
     ds = good_tl(); ds.struct_size = 4
     assert B.rl_token_logprob_raw(ds) == -4
     assert B._lib.rl_token_logprob(None, None) == -1
+
+
+# ---------------------------------------------------------------- rl_kv_append_rope
+def good_ka(**kw):
+    args = dict(dtype=B.RLDA_BF16, B=4, Hq=8, Hkv=2, d=128, sections=(16, 24, 24), Ls_cap=64)
+    args.update(kw)
+    return B.make_kv_append_desc(**args)
+
+
+def test_kv_append_descriptor_layout_and_errors():
+    assert ctypes.sizeof(B.rl_kv_append_desc) == 56 + 10 * 8
+    assert B.rl_kv_append_desc.q.offset == 56
+    fake = 0x1000
+    ptrs = dict(q=fake, k_new=fake, v_new=fake, positions=fake, inv_freq=fake, k_store=fake, v_store=fake, suffix_lens=fake)
+    for kw, code in [(dict(d=96), -2), (dict(sections=(16, 24, 23)), -2), (dict(sections=(-1, 41, 24)), -2),
+                     (dict(dtype=7), -2), (dict(Hkv=0), -1), (dict(B=-1), -1), (dict(Ls_cap=-1), -1),
+                     (dict(block_table=fake, page_size=48, max_pages=2, n_pages=4), -2),
+                     (dict(block_table=fake, page_size=64, max_pages=2, n_pages=0), -1)]:
+        assert B.rl_kv_append_rope_raw(good_ka(**ptrs, **kw)) == code, kw
+    assert B.rl_kv_append_rope_raw(good_ka()) == -1                  # null tensors
+    assert B.rl_kv_append_rope_raw(good_ka(B=0)) == 0
+    ds = good_ka(**ptrs); ds.struct_size = 16
+    assert B.rl_kv_append_rope_raw(ds) == -4
+    assert B._lib.rl_kv_append_rope(None, None) == -1

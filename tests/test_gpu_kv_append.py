@@ -1,0 +1,180 @@
+"""GPU parity of rl_kv_append_rope against the oracle, through the C ABI.
+
+Bar: lengths, value rows and every untouched row bit-exact; rotated values within 2e-6 * (1 + |x|)
+for fp32 (one fp32 rounding of a two-term sum against fp64) and, for bf16, equal to the oracle's
+bf16 value except where the fp32 result sits on a rounding boundary: at most one bf16 step apart
+and at least 99.9 % identical.
+"""
+import numpy as np
+import pytest
+
+from oracle.kv_append_ref import kv_append_rope_ref
+from paper_2512_21450_amd import workloads as wl
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2512_21450_amd import binding
+    return binding
+
+
+def dev(a):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def host(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def close(got, want, what):
+    if want.dtype == np.uint16:
+        g, w = wl.bf16_bits_to_f32(got).astype(np.float64), wl.bf16_bits_to_f32(want).astype(np.float64)
+        same = got == want
+        assert same.mean() >= 0.999, f"{what}: only {same.mean():.5f} of the bf16 values identical"
+        assert (np.abs(g - w) <= 2.0 ** -7 * np.abs(w) + 1e-30).all(), f"{what}: more than one bf16 step apart"
+    else:
+        assert (np.abs(got.astype(np.float64) - want) <= 2e-6 * (1 + np.abs(want))).all(), what
+
+
+def run_case(B, w, x, store, nt, table=None, active=None, what=""):
+    """store: dict with k, v (contiguous or pools) and lens"""
+    import torch
+    t = {k: dev(v) for k, v in nt.items() if isinstance(v, np.ndarray)}
+    ks, vs, lens = dev(store["k"]), dev(store["v"]), dev(store["lens"])
+    tb = None if table is None else dev(table)
+    act = None if active is None else torch.from_numpy(active).cuda()
+    B.rl_kv_append_rope(t["q"], t["k_new"], t["v_new"], t["positions"], t["inv_freq"], nt["sections"], ks, vs, lens,
+                        block_table=tb, seq_active=act)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref, l_ref = kv_append_rope_ref(nt["q"], nt["k_new"], nt["v_new"], nt["positions"], nt["inv_freq"],
+                                                    nt["sections"], store["k"], store["v"], store["lens"],
+                                                    block_table=table, seq_active=active)
+    assert np.array_equal(host(lens), l_ref), f"{what}: lengths"
+    assert np.array_equal(host(vs), v_ref), f"{what}: value store"
+    close(host(t["q"]), q_ref, f"{what}: q")
+    gk = host(ks)
+    changed = (k_ref != store["k"])
+    assert np.array_equal(gk[~changed], store["k"][~changed]), f"{what}: a key row that was not the target changed"
+    close(gk, k_ref, f"{what}: key store")
+
+
+@pytest.mark.parametrize("name", ["tiny", "vlm3b", "vlm7b"])
+def test_contiguous_store(B, name):
+    w = wl.WORKLOADS[name]
+    if name == "vlm7b":
+        w = wl.scaled(w, P=8)
+    x = wl.make_inputs(w)
+    nt = wl.make_new_token(w, x, seed=w.seed + 1)
+    lens = np.minimum(x["suffix_lens"], w.Ls_cap - 1).astype(np.int32)
+    lens[0] = w.Ls_cap                         # full: skipped
+    lens[1] = -7                               # nonsense: skipped
+    run_case(B, w, x, dict(k=x["k_suffix"], v=x["v_suffix"], lens=lens), nt, what=name)
+
+
+@pytest.mark.parametrize("ps", [32, 128])
+def test_paged_store_with_finished_sequences(B, ps):
+    w = wl.scaled(wl.WORKLOADS["vlm7b"], P=4, Ls_cap=512, suffix=("uniform", 500))
+    x = wl.make_inputs(w)
+    full = dict(x); full["suffix_lens"] = np.full(w.B, 512, np.int32)
+    y = wl.to_pages(full, ps, seed=3, poison=False)
+    nt = wl.make_new_token(w, x, seed=77)
+    act = (np.arange(w.B) % 3 != 0).astype(np.uint8)
+    lens = x["suffix_lens"].copy(); lens[5] = 512; lens[7] = 0; lens[9] = ps - 1; lens[10] = ps
+    run_case(B, w, x, dict(k=y["k_pages"], v=y["v_pages"], lens=lens), nt, table=y["block_table"], active=act,
+             what=f"paged {ps}")
+
+
+def test_large_positions_keep_their_accuracy(B):
+    w = wl.scaled(wl.WORKLOADS["vlm3b"], P=2)
+    x = wl.make_inputs(w)
+    nt = wl.make_new_token(w, x, seed=5)
+    nt["positions"] = (nt["positions"].astype(np.int64) + 120_000).astype(np.int32)   # long multi-turn contexts
+    run_case(B, w, x, dict(k=x["k_suffix"], v=x["v_suffix"], lens=np.minimum(x["suffix_lens"], 500).astype(np.int32)),
+             nt, what="positions 120k")
+
+
+def test_append_then_attend_loop_in_a_graph(B):
+    """Two full decode steps (state transition, then attention over the grown store) recorded once and
+    replayed: every replay equals the eager run, and the eager run equals the oracles chained."""
+    import torch
+    w = wl.scaled(wl.WORKLOADS["vlm7b"], P=3, Ls_cap=256, suffix=("uniform", 200))
+    x = wl.make_inputs(w)
+    full = dict(x); full["suffix_lens"] = np.full(w.B, 256, np.int32)
+    y = wl.to_pages(full, 64, seed=4, poison=False)
+    steps = 2
+    nts = [wl.make_new_token(w, x, seed=90 + i) for i in range(steps)]
+    for i, nt in enumerate(nts):
+        nt["positions"] = nt["positions"] + i
+    act_np = (np.arange(w.B) % 4 != 2).astype(np.uint8)
+    # oracle chain
+    kp, vp, lens = y["k_pages"], y["v_pages"], x["suffix_lens"].copy()
+    want = []
+    for nt in nts:
+        q_rot, kp, vp, lens = kv_append_rope_ref(nt["q"], nt["k_new"], nt["v_new"], nt["positions"], nt["inv_freq"],
+                                                 nt["sections"], kp, vp, lens, block_table=y["block_table"],
+                                                 seq_active=act_np)
+        yy = dict(y, k_pages=kp, v_pages=vp, suffix_lens=lens, q=q_rot)
+        want.append(util.oracle_paged(yy, w.scale, w.G, active=act_np))
+    # device state
+    t = util.to_device(y)
+    act = torch.from_numpy(act_np).cuda()
+    k0, v0, l0 = t["k_pages"].clone(), t["v_pages"].clone(), dev(x["suffix_lens"])
+    lens_d = l0.clone()
+    dn = [{k: dev(v) for k, v in nt.items() if isinstance(v, np.ndarray)} for nt in nts]
+    q0 = [d["q"].clone() for d in dn]
+    outs = [torch.empty((w.B, w.Hq, w.d), dtype=torch.float32, device="cuda") for _ in range(steps)]
+    lses = [torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda") for _ in range(steps)]
+    ds0 = B.paged_desc_from_tensors(dn[0]["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_pages"],
+                                    t["v_pages"], t["block_table"], lens_d, w.scale, w.G, outs[0], lses[0], act)
+    ws = torch.empty(B.rl_decode_attn_paged_workspace_bytes(ds0), dtype=torch.uint8, device="cuda")
+
+    def reset():
+        t["k_pages"].copy_(k0); t["v_pages"].copy_(v0); lens_d.copy_(l0)
+        for d, q in zip(dn, q0):
+            d["q"].copy_(q)
+
+    def run_steps():
+        s = torch.cuda.current_stream()
+        for i in range(steps):
+            B.rl_kv_append_rope(dn[i]["q"], dn[i]["k_new"], dn[i]["v_new"], dn[i]["positions"], dn[i]["inv_freq"],
+                                nts[i]["sections"], t["k_pages"], t["v_pages"], lens_d, block_table=t["block_table"],
+                                seq_active=act, stream=s)
+            ds = B.paged_desc_from_tensors(dn[i]["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_pages"],
+                                           t["v_pages"], t["block_table"], lens_d, w.scale, w.G, outs[i], lses[i],
+                                           act, ws)
+            assert B.rl_decode_attn_paged_raw(ds, s.cuda_stream, None) == 0
+
+    run_steps()
+    torch.cuda.synchronize()
+    for i in range(steps):
+        util.compare(outs[i], lses[i], want[i][0], want[i][1], "bf16", f"eager step {i}")
+    eager = [(o.clone(), l.clone()) for o, l in zip(outs, lses)]
+    assert np.array_equal(host(lens_d), lens)
+    reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(g, stream=side):
+            run_steps()
+    for rep in range(3):
+        reset()
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for i in range(steps):
+            assert torch.equal(outs[i], eager[i][0]) and torch.equal(lses[i], eager[i][1]), f"replay {rep} step {i}"
+        assert np.array_equal(host(lens_d), lens)
