@@ -295,3 +295,43 @@ def test_profiled_entry_point_records_the_middle_event(B):
     assert 0.0 < e0.elapsed_time(em) <= e0.elapsed_time(e1)
     ro, rl = util.oracle(x, w.scale, w.G)
     util.compare(out, lse, ro, rl, "bf16", "profiled")
+
+
+def test_two_level_shared_prefix_by_composition(B):
+    """A prefix tree (prompt shared by the group, a first turn shared by sub-groups, own suffix) needs no
+    new kernel: one call per level yields (o, lse) partials over disjoint key sets and rl_lse_combine
+    merges them.  Checked against the oracle on the concatenated keys."""
+    import torch
+    P, G, sub, Hq, Hkv, d = 3, 8, 4, 28, 4, 128
+    L0, L1, Ls = 300, 150, 90
+    rng = np.random.default_rng(61)
+    t16 = lambda shape: wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+    q = t16((P * G, Hq, d))
+    k0, v0 = t16((P, Hkv, L0, d)), t16((P, Hkv, L0, d))                       # level 0: one per prompt
+    k1, v1 = t16((P * G // sub, Hkv, L1, d)), t16((P * G // sub, Hkv, L1, d))  # level 1: one per sub-group
+    ks, vs = t16((P * G, Hkv, Ls, d)), t16((P * G, Hkv, Ls, d))
+    len0 = rng.integers(1, L0 + 1, P).astype(np.int32)
+    len1 = rng.integers(0, L1 + 1, P * G // sub).astype(np.int32)
+    lens = rng.integers(0, Ls + 1, P * G).astype(np.int32)
+    # oracle: level 1 and the own suffix concatenated per sequence behind the prompt
+    cat_k = np.zeros((P * G, Hkv, L1 + Ls, d), np.uint16); cat_v = np.zeros_like(cat_k)
+    cat_len = np.zeros(P * G, np.int32)
+    for b in range(P * G):
+        a, n = int(len1[b // sub]), int(lens[b])
+        cat_k[b, :, :a] = k1[b // sub, :, :a]; cat_v[b, :, :a] = v1[b // sub, :, :a]
+        cat_k[b, :, a:a + n] = ks[b, :, :n]; cat_v[b, :, a:a + n] = vs[b, :, :n]
+        cat_len[b] = a + n
+    from oracle import ref
+    ro, rl = ref.decode_attn_ref(q, k0, v0, len0, cat_k, cat_v, cat_len, 0.09, G)
+    # GPU: level 0 with no suffix; level 1 as the "prefix" of groups of `sub` plus the own suffix; merge
+    dev = lambda a: (torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16) if a.dtype == np.uint16
+                     else torch.from_numpy(a).cuda())
+    qd = dev(q)
+    zero = torch.zeros(P * G, dtype=torch.int32, device="cuda")
+    o0, l0 = B.rl_decode_attn(qd, dev(k0), dev(v0), dev(len0), dev(ks), dev(vs), zero, 0.09, G)
+    o1, l1 = B.rl_decode_attn(qd, dev(k1), dev(v1), dev(len1), dev(ks), dev(vs), dev(lens), 0.09, sub)
+    parts_o = torch.stack([o0.reshape(-1, d), o1.reshape(-1, d)])
+    parts_l = torch.stack([l0.reshape(-1), l1.reshape(-1)])
+    out, lse = B.rl_lse_combine(parts_o, parts_l)
+    torch.cuda.synchronize()
+    util.compare(out.reshape(P * G, Hq, d), lse.reshape(P * G, Hq), ro, rl, "bf16", "two-level prefix")
