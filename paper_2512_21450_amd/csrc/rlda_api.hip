@@ -193,7 +193,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
       int p, j, t;
       locate(X.data(), P, Hkv, ilo, p, j, t);
       for_each_run(ilo, ihi, P, Hkv, p, j, t, tp,
-                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * Hkv + jj + w); });
+                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * Hkv + jj + wg_rank(sc, w)); });
     }
     for (int v = 0; v < WG_WAVES; ++v) {
       int ka, kb;
@@ -202,7 +202,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
       int b, j, t;
       locate(X.data() + P, B, Hkv, ka + cumP * Hkv, b, j, t);
       for_each_run(ka, kb, B, Hkv, b, j, t, ts, [&](int bb, int jj, int t0, int n) {
-        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * suffix_wg_rank(sc, w) + v);
+        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * wg_rank(sc, w) + v);
       });
     }
   }
@@ -215,7 +215,9 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
   };
   for (int p = 0; p < P; ++p)                    // the combine kernel's enumeration
     for (int j = 0; j < Hkv; ++j)
-      for_each_prefix_part(sc, X.data(), Hkv, p, j, [&](int w) { put_part(0, p, j, w, -1, p * Hkv + j + w); });
+      for_each_prefix_part(sc, X.data(), Hkv, p, j, [&](int rank) {
+        put_part(0, p, j, rank % 2 ? N_CU + rank / 2 : rank / 2, -1, p * Hkv + j + rank);
+      });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)
       for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j, [&](int rank, int v) {

@@ -9,20 +9,21 @@
 // The partial kernel runs 2 * N_CU workgroups, two per compute unit: workgroup
 // c ("A") and workgroup N_CU + c ("B") form pair c.  Every pair gets the same
 // share of each line (position N*c/N_CU .. N*(c+1)/N_CU), so that every compute
-// unit carries the same mix of work and all finish together.  A takes the pair's
-// prefix tiles, which the whole workgroup processes together (one shared K/V
-// tile in LDS, 16-row query blocks spread over the wavefronts), plus the first
-// xA of the pair's suffix tiles; B takes the rest of the suffix tiles.  xA
-// evens out the two by tile weight (a prefix tile costs wP, a suffix tile wS:
-// prefix tiles carry several times the matrix work per byte).  A workgroup's
-// suffix tiles are cut into WG_WAVES consecutive runs, one per wavefront.
-// While A works through prefix tiles, which are bound by matrix and LDS work, B
-// streams suffix tiles, which are bound by memory, on the same compute unit.
+// unit carries the same mix of work and all finish together.  Inside a pair the
+// two workgroups are evened out by tile weight (a prefix tile costs wP, a suffix
+// tile wS): in a batch whose suffix tiles outweigh its prefix tiles, A takes all
+// prefix tiles plus the first few suffix tiles and B the other suffix tiles; in
+// a prefix-heavy batch (short responses behind long multimodal prompts, the
+// first steps of any rollout), A takes prefix tiles only and B the last few
+// prefix tiles plus all suffix tiles.  A workgroup processes its
+// prefix tiles together (one shared K/V tile in LDS, 16-row query blocks spread
+// over the wavefronts) and then cuts its suffix tiles into WG_WAVES consecutive
+// runs, one per wavefront.
 //
 // Every maximal run of tiles of one unit inside one workgroup (prefix) or one
-// wavefront (suffix) yields one partial (o, lse); its slot is unit + c (prefix)
-// or unit + WG_WAVES*(2c + [B]) + wavefront (suffix), unique because both terms
-// are monotone along the line.  Nothing here depends on run-time timing, so
+// wavefront (suffix) yields one partial (o, lse); its slot is unit + (2c + [B])
+// (prefix) or unit + WG_WAVES*(2c + [B]) + wavefront (suffix), unique because
+// both terms are monotone along the line.  Nothing here depends on run-time timing, so
 // the split and hence the rounding order is the same on every call.
 #pragma once
 
@@ -42,6 +43,7 @@ struct Sched {
   int NST;      // suffix tiles in total
   int wP, wS;   // tile weights
   int n_cu;     // workgroup pairs
+  bool heavy;   // the prefix tiles outweigh the suffix tiles: B workgroups share them, A takes no suffix
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
@@ -50,6 +52,7 @@ __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? l
 __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {
   Sched s;
   s.NPT = NPT; s.NST = NST; s.wP = wP; s.wS = wS; s.n_cu = n_cu;
+  s.heavy = wP * NPT > wS * NST;               // lines are at most MAX_LINE tiles: no overflow
   return s;
 }
 
@@ -64,20 +67,34 @@ __host__ __device__ inline int share_owner(int N, int i, int n_cu) {
   return (int)((((unsigned)(i + 1) * (unsigned)n_cu) + (unsigned)N - 1u) / (unsigned)N) - 1;
 }
 
-// prefix tiles [lo, hi) of workgroup w (B workgroups have none)
-__host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
-  if (w >= s.n_cu) { lo = hi = 0; return; }
-  lo = share(s.NPT, w, s.n_cu);
-  hi = share(s.NPT, w + 1, s.n_cu);
+// prefix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  B gets some only
+// in a prefix-heavy batch, and then as many as even out the pair.
+__host__ __device__ inline void pair_prefix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
+  lo = share(s.NPT, c, s.n_cu);
+  hi = share(s.NPT, c + 1, s.n_cu);
+  mid = hi;
+  if (s.heavy) {
+    const int ns = share(s.NST, c + 1, s.n_cu) - share(s.NST, c, s.n_cu);
+    mid = hi - clampi((s.wP * (hi - lo) - s.wS * ns) / (2 * s.wP), 0, hi - lo);
+  }
 }
-__host__ __device__ inline int prefix_tile_owner(const Sched& s, int i) { return share_owner(s.NPT, i, s.n_cu); }
+__host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
+  int a, m, b;
+  pair_prefix_range(s, w % s.n_cu, a, m, b);
+  if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
+}
+__host__ __device__ inline int prefix_tile_pair(const Sched& s, int i) { return share_owner(s.NPT, i, s.n_cu); }
 
-// suffix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi)
+// suffix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  A gets some only
+// in a suffix-heavy batch, and then as many as even out the pair.
 __host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
   lo = share(s.NST, c, s.n_cu);
   hi = share(s.NST, c + 1, s.n_cu);
-  const int np = share(s.NPT, c + 1, s.n_cu) - share(s.NPT, c, s.n_cu);
-  mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
+  mid = lo;
+  if (!s.heavy) {
+    const int np = share(s.NPT, c + 1, s.n_cu) - share(s.NPT, c, s.n_cu);
+    mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
+  }
 }
 __host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
   int a, m, b;
@@ -96,8 +113,8 @@ __host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {
   const int q = ceil_div(hi - lo, WG_WAVES);
   return (k - lo) / q;
 }
-// slot term of workgroup w on the suffix line (A and B of a pair are neighbours there)
-__host__ __device__ inline int suffix_wg_rank(const Sched& s, int w) { return w < s.n_cu ? 2 * w : 2 * (w - s.n_cu) + 1; }
+// slot term of workgroup w on either line (A and B of a pair are neighbours there, A first)
+__host__ __device__ inline int wg_rank(const Sched& s, int w) { return w < s.n_cu ? 2 * w : 2 * (w - s.n_cu) + 1; }
 
 // ---- walking the line -------------------------------------------------------------------
 // X is the exclusive scan of per-head tile counts over `n` prompts (or sequences); every
@@ -132,16 +149,17 @@ __host__ __device__ inline void for_each_run(int lo, int hi, int n, int Hkv, int
   }
 }
 
-// Workgroups holding a partial of prefix unit (p, j): fn(c) in increasing c.  Xp = scan over prompts.
+// Workgroups (by rank) holding a partial of prefix unit (p, j): fn(rank) in line order.  Xp = scan over prompts.
 template <class Fn>
 __host__ __device__ inline void for_each_prefix_part(const Sched& s, const int* Xp, int Hkv, int p, int j, Fn fn) {
   const int T = Xp[p + 1] - Xp[p];
   if (T <= 0) return;
   const int is = Xp[p] * Hkv + j * T, ie = is + T;
-  for (int c = prefix_tile_owner(s, is); c <= prefix_tile_owner(s, ie - 1); ++c) {
-    int lo, hi;                                  // with fewer tiles than pairs some own nothing
-    wg_prefix_range(s, c, lo, hi);
-    if ((lo > is ? lo : is) < (hi < ie ? hi : ie)) fn(c);
+  for (int c = prefix_tile_pair(s, is); c <= prefix_tile_pair(s, ie - 1); ++c) {
+    int lo, mid, hi;                             // with fewer tiles than pairs some own nothing
+    pair_prefix_range(s, c, lo, mid, hi);
+    if ((lo > is ? lo : is) < (mid < ie ? mid : ie)) fn(2 * c);
+    if (s.heavy && (mid > is ? mid : is) < (hi < ie ? hi : ie)) fn(2 * c + 1);
   }
 }
 

@@ -272,7 +272,7 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, in
 // boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
 // merged through LDS and the partial is written.
 template <int NRB, int NT, bool EXT>
-__device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int w, int tid) {
+__device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int tid) {
   auto len_of = [&](int p) { return plen_of<EXT>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   constexpr int LPS = 8 / NRB;                              // loads (of K and of V) per slice
@@ -416,7 +416,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
         }
         lds_barrier();                                      // parked state is dead before tiles are stored again
       }
-      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.Hkv + cur.j + w, P.R, rowbase, lane);
+      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.Hkv + cur.j + rank, P.R, rowbase, lane);
     }
     fresh = next_fresh; cur = nxt; rem = rem2; gs = ngs;
   }
@@ -545,12 +545,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
     cur_load(c, [&](int p) { return plen_of<EXT>(P, p); });
-    prefix_stream<NRB, NT, EXT>(P, lds, c, ihi - ilo, w, tid);
+    prefix_stream<NRB, NT, EXT>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
     cur_load(c, [&](int b) { return slen_of<EXT>(P, b); });
-    suffix_stream<EXT>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * suffix_wg_rank(sc, w) + wv, lane);
+    suffix_stream<EXT>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane);
   }
 }
 
@@ -644,7 +644,7 @@ struct Layout { size_t cum, pl, po, sl, so, total; };
 
 Layout layout(const Problem& ds) {
   const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, R = r * ds.G;
-  const size_t nps = (size_t)ds.P * ds.Hkv + N_CU, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
+  const size_t nps = (size_t)ds.P * ds.Hkv + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
   size_t o = 0;
   L.cum = o; o = align256(o + (ds.P + B + 1) * 4);

@@ -50,7 +50,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
                 assert pos == T, (kind, major, j, segs, T)
         assert not seen
     # slots: unique per kind, inside the workspace the library sizes
-    for kind, nslots in ((0, P * Hkv + 256), (1, P * G * Hkv + 8 * 256)):
+    for kind, nslots in ((0, P * Hkv + 512), (1, P * G * Hkv + 8 * 256)):
         sl = runs[runs[:, 0] == kind][:, 7]
         assert len(set(sl.tolist())) == len(sl)
         assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
@@ -67,49 +67,22 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
         np.add.at(load, rk[:, 5] % 256, rk[:, 4])
         assert load.sum() == total
         assert load.max() <= -(-total // 256) and load.min() >= total // 256
-    assert not (runs[(runs[:, 0] == 0)][:, 5] >= 256).any()      # prefix tiles go to the first workgroup of a pair
-    return runs[:nr], parts[:npart.value]
-
-
-def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
-    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens)
-    tp = -(-np.clip(plens, 0, Lp_cap) // TK)
-    ts = -(-np.clip(slens, 0, Ls_cap) // TK)
-    # coverage: each unit's tiles [0, T) are tiled by its runs without gap or overlap
-    for kind, counts in ((0, tp), (1, ts)):
-        rk = runs[runs[:, 0] == kind]
-        seen = {}
-        for _, major, j, t0, n, w, v, slot in rk:
-            assert n > 0
-            seen.setdefault((major, j), []).append((t0, n))
-        for major, T in enumerate(counts):
-            for j in range(Hkv):
-                segs = sorted(seen.pop((major, j), []))
-                pos = 0
-                for t0, n in segs:
-                    assert t0 == pos, (kind, major, j, segs)
-                    pos += n
-                assert pos == T, (kind, major, j, segs, T)
-        assert not seen
-    # slots: unique per kind, inside the workspace the library sizes
-    for kind, nslots in ((0, P * Hkv + 256), (1, P * G * Hkv + 8 * 256)):
-        sl = runs[runs[:, 0] == kind][:, 7]
-        assert len(set(sl.tolist())) == len(sl)
-        assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
-    # the combine enumeration == the set of runs, and per unit in increasing line order
-    key_r = sorted((int(k), int(m), int(j), int(w), int(v), int(s)) for k, m, j, _, _, w, v, s in runs)
-    key_p = sorted(tuple(int(x) for x in row) for row in parts)
-    assert key_r == key_p
-    # balance: the two workgroups of a pair (w and 256 + w share a compute unit) together hold
-    # an equal share of the prefix tiles and of the suffix tiles, up to rounding
-    npt, nst = int(tp.sum()) * Hkv, int(ts.sum()) * Hkv
-    for kind, total in ((0, npt), (1, nst)):
-        load = np.zeros(256, np.int64)
-        rk = runs[runs[:, 0] == kind]
-        np.add.at(load, rk[:, 5] % 256, rk[:, 4])
-        assert load.sum() == total
-        assert load.max() <= -(-total // 256) and load.min() >= total // 256
-    assert not (runs[(runs[:, 0] == 0)][:, 5] >= 256).any()      # prefix tiles go to the first workgroup of a pair
+    # inside a pair the heavier line is shared: the second workgroup has prefix tiles only if the first
+    # has no suffix tiles, and the two then differ by less than two tiles' weight
+    WP, WS = 6, 4
+    wa, wb = np.zeros(256, np.int64), np.zeros(256, np.int64)
+    a_suffix, b_prefix = np.zeros(256, np.int64), np.zeros(256, np.int64)
+    for kind, _, _, _, n, w, _, _ in runs:
+        wt = n * (WP if kind == 0 else WS)
+        if w < 256:
+            wa[w] += wt
+            a_suffix[w] += n if kind == 1 else 0
+        else:
+            wb[w - 256] += wt
+            b_prefix[w - 256] += n if kind == 0 else 0
+    assert not ((a_suffix > 0) & (b_prefix > 0)).any()
+    shared = (a_suffix > 0) | (b_prefix > 0)
+    assert (np.abs(wa - wb)[shared] <= 2 * max(WP, WS)).all()
     return runs
 
 
@@ -121,6 +94,24 @@ def test_partition_of_the_benchmark_workloads(name):
     sl = wl._draw_lens(rng, w.suffix, w.B, w.Ls_cap)
     runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl)
     assert len(runs) > 0
+
+
+def test_prefix_heavy_batches_put_prefix_tiles_on_both_workgroups():
+    # long prompts, a few generated tokens: the first steps of a rollout, or short answers
+    w = wl.WORKLOADS["vlm7b"]
+    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, [w.Lp_cap] * w.P, [5] * w.B)
+    pre = runs[runs[:, 0] == 0]
+    on_b = pre[pre[:, 5] >= 256][:, 4].sum()
+    assert 0.35 * pre[:, 4].sum() < on_b < 0.5 * pre[:, 4].sum()
+    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, [w.Lp_cap] * w.P, [0] * w.B)     # no suffix at all: halves
+    pre = runs[runs[:, 0] == 0]
+    assert abs(int(pre[pre[:, 5] >= 256][:, 4].sum()) * 2 - int(pre[:, 4].sum())) <= 256
+    # suffix-heavy: every prefix tile on the first workgroup of a pair
+    rng = np.random.default_rng(w.seed)
+    pl = wl._draw_lens(rng, w.prefix, w.P, w.Lp_cap)
+    sl = wl._draw_lens(rng, w.suffix, w.B, w.Ls_cap)
+    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl)
+    assert not (runs[runs[:, 0] == 0][:, 5] >= 256).any()
 
 
 def test_partition_edge_cases():
