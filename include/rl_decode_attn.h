@@ -216,7 +216,9 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
 /*
  * Testing hook, pure host code: the static work partition the shared-prefix
  * path uses for the given lengths (HOST arrays prefix_lens [P], suffix_lens
- * [P*G]).  `runs` receives one row of 8 int32 per run of tiles a workgroup
+ * [P*G]; rows_per_kv_group = G * Hq / Hkv).  When a KV group has more than 64
+ * query rows its prefix units are (prompt, KV head, row half) and the "KV head"
+ * column of a prefix row holds 2 * head + half.  `runs` receives one row of 8 int32 per run of tiles a workgroup
  * (prefix) or wavefront (suffix) processes: kind (0 prefix, 1 suffix), prompt
  * or sequence, KV head, first tile, tile count, workgroup, wavefront (-1 for
  * prefix), partial slot.  `parts` receives one row of 6 int32 per partial the
@@ -225,7 +227,8 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
  * number of runs (or RLDA_ERR_INVALID) and stores the number of parts in
  * *n_parts.  Tiles are 32 keys.
  */
-int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t Lp_cap, int32_t Ls_cap,
+int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t rows_per_kv_group,
+                                       int32_t Lp_cap, int32_t Ls_cap,
                                        const int32_t* prefix_lens, const int32_t* suffix_lens,
                                        int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
                                        int64_t* n_parts);

@@ -163,20 +163,22 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
   return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
 }
 
-int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t Lp_cap, int32_t Ls_cap,
-                                       const int32_t* prefix_lens, const int32_t* suffix_lens,
+int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t rows_per_kv_group,
+                                       int32_t Lp_cap, int32_t Ls_cap, const int32_t* prefix_lens, const int32_t* suffix_lens,
                                        int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
                                        int64_t* n_parts) {
   using namespace rlda;
-  if (P < 0 || G < 0 || Hkv <= 0 || !prefix_lens || !suffix_lens || !n_parts) return RLDA_ERR_INVALID;
+  if (P < 0 || G < 0 || Hkv <= 0 || rows_per_kv_group <= 0 || !prefix_lens || !suffix_lens || !n_parts)
+    return RLDA_ERR_INVALID;
   const int B = P * G;
+  const int HkvP = Hkv * (rows_per_kv_group > 16 * WG_WAVES ? 2 : 1);   // prefix units per prompt: (KV head, row half)
   std::vector<int> X(P + B + 2, 0);
   auto tp = [&](int p) { return ceil_div(clampi(prefix_lens[p], 0, Lp_cap), TK); };
   auto ts = [&](int b) { return ceil_div(clampi(suffix_lens[b], 0, Ls_cap), TK); };
   for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
   for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
   const int cumP = X[P];
-  const Sched sc = make_sched(cumP * Hkv, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   int64_t nr = 0, np = 0;
   auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
     if (runs && nr < runs_cap) {
@@ -191,9 +193,9 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
     wg_suffix_range(sc, w, klo, khi);
     if (ilo < ihi) {
       int p, j, t;
-      locate(X.data(), P, Hkv, ilo, p, j, t);
-      for_each_run(ilo, ihi, P, Hkv, p, j, t, tp,
-                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * Hkv + jj + wg_rank(sc, w)); });
+      locate(X.data(), P, HkvP, ilo, p, j, t);
+      for_each_run(ilo, ihi, P, HkvP, p, j, t, tp,
+                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * HkvP + jj + wg_rank(sc, w)); });
     }
     for (int v = 0; v < WG_WAVES; ++v) {
       int ka, kb;
@@ -214,9 +216,9 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
     ++np;
   };
   for (int p = 0; p < P; ++p)                    // the combine kernel's enumeration
-    for (int j = 0; j < Hkv; ++j)
-      for_each_prefix_part(sc, X.data(), Hkv, p, j, [&](int rank) {
-        put_part(0, p, j, rank % 2 ? N_CU + rank / 2 : rank / 2, -1, p * Hkv + j + rank);
+    for (int j = 0; j < HkvP; ++j)
+      for_each_prefix_part(sc, X.data(), HkvP, p, j, [&](int rank) {
+        put_part(0, p, j, rank % 2 ? N_CU + rank / 2 : rank / 2, -1, p * HkvP + j + rank);
       });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)

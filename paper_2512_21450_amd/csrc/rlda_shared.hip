@@ -52,6 +52,11 @@ struct SharedParams {
   float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
+  // The R = G * r query rows of a KV group are handled as NH row halves of at most 64 rows (NH = 2
+  // when R > 64): a prefix unit is (prompt, KV head, half), numbered jp = j * NH + half, so that a
+  // wavefront never carries more than one 16-row block.  HkvP = Hkv * NH units per prompt; a prefix
+  // partial slot holds RS rows.
+  int NH, HkvP, RS;
   float c;                // scale * log2(e): scores are kept in base 2
   // extended form only (kernels instantiated with EXT = true):
   const int32_t* table;   // [B, max_pages] page ids when ks / vs are page pools [n_pages, Hkv, page, D], else null
@@ -277,9 +282,10 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   constexpr int LPS = 8 / NRB;                              // loads (of K and of V) per slice
   const int rb = wv & (NRB - 1), part = wv / NRB, s_lo = part * NRB;
-  const int rowbase = 16 * NT * rb;
-  const bool active = rowbase < P.R;
+  const int rowbase = 16 * NT * rb;                         // inside the unit's row half
   const int lrow = lane >> 4, chunk = lane & 15;
+  auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
+  auto head_of = [&](const Cur& c) { return c.j >> (P.NH - 1); };
   char* mine = lds + wv * STAGE_B;
 
   constexpr bool QPRE = NT == 1;                            // NT = 2 has no registers left for a query prefetch
@@ -289,9 +295,9 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   auto issue_q = [&](const Cur& c) {                        // row = sample * r + head-in-group
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-      const int row = rowbase + 16 * nt + m16;
+      const int row = 64 * half_of(c) + rowbase + 16 * nt + m16;
       const bool ok = row < P.R;
-      const int b = c.u * P.G + (ok ? row / P.r : 0), h = c.j * P.r + (ok ? row % P.r : 0);
+      const int b = c.u * P.G + (ok ? row / P.r : 0), h = head_of(c) * P.r + (ok ? row % P.r : 0);
       const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
@@ -305,8 +311,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   int rem = n, gs = group_size(cur, rem);
   if (QPRE) issue_q(cur);
   if (wv < gs) {
-    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
-    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + cur.j) * P.Lp_cap * ROWB;
+    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * ROWB;
+    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * ROWB;
     const int key0 = (cur.t + wv) * TK, last = min(TK, cur.L - key0) - 1;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -317,6 +323,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   }
   bool fresh = true;
   while (rem > 0) {
+    const bool active = 64 * half_of(cur) + rowbase < P.R;  // this wavefront's row block exists in the unit's half
     wait_vmem();
     if (wv < gs) {
 #pragma unroll
@@ -342,15 +349,15 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
     int ngs = 0;
     bool next_fresh = false;
     if (rem2 > 0) {
-      cur_step(nxt, gs, len_of, P.P, P.Hkv);
+      cur_step(nxt, gs, len_of, P.P, P.HkvP);
       ngs = group_size(nxt, rem2);
       next_fresh = nxt.u != cur.u || nxt.j != cur.j;
     }
     lds_barrier();
     if (QPRE && next_fresh) issue_q(nxt);
     const bool more = wv < ngs;                             // this wavefront fetches a tile of the next group
-    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
-    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + nxt.j) * P.Lp_cap * ROWB;
+    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * ROWB;
+    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * ROWB;
     const int key0 = (nxt.t + wv) * TK, last = min(TK, nxt.L - key0) - 1;
     // the upper half of the wavefronts issues a slice before each tile computation, the lower half
     // after it, so that they alternate between the memory pipeline and the matrix pipeline
@@ -416,7 +423,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
         }
         lds_barrier();                                      // parked state is dead before tiles are stored again
       }
-      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.Hkv + cur.j + rank, P.R, rowbase, lane);
+      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.HkvP + cur.j + rank, P.RS, rowbase, lane);
     }
     fresh = next_fresh; cur = nxt; rem = rem2; gs = ngs;
   }
@@ -524,7 +531,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -533,7 +540,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   wg_suffix_range(sc, w, klo, khi);
   wave_suffix_range(klo, khi, wv, ka, kb);
   int pp = 0, pj = 0, pt = 0, sb = 0, sj = 0, st0 = 0;
-  if (ilo < ihi) locate_wave(X, P.P, P.Hkv, ilo, lane, pp, pj, pt);
+  if (ilo < ihi) locate_wave(X, P.P, P.HkvP, ilo, lane, pp, pj, pt);
   if (ka < kb) {
     locate_wave(X + P.P, P.B, P.Hkv, ka + cumP * P.Hkv, lane, sb, sj, st0);   // X + P continues the prompt scan: shift the line
   }
@@ -571,16 +578,18 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.Hkv, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
-  const int prow = gs * P.r + hi_;                          // row inside the prefix unit: sample-major
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
+  const int half = P.NH == 2 ? grow >> 6 : 0;
+  const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
 
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float M = -INFINITY, Z = 0.f;                             // running max and sum over batches of 32 parts
   for (int base = 0;; base += 32) {
     // part `base + sub` of this row, as 2 * (row index in its partial array) + [suffix]
     int n = 0, mine = -1;
-    for_each_prefix_part(sc, X, P.Hkv, p, j, [&](int c) {
-      if (n == base + sub) mine = 2 * ((p * P.Hkv + j + c) * P.R + prow);
+    for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
+      if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
       ++n;
     });
     for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
@@ -643,8 +652,9 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct Layout { size_t cum, pl, po, sl, so, total; };
 
 Layout layout(const Problem& ds) {
-  const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, R = r * ds.G;
-  const size_t nps = (size_t)ds.P * ds.Hkv + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
+  const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, Rg = r * ds.G;
+  const size_t NH = Rg > 64 ? 2 : 1, R = NH == 2 ? 64 : Rg;   // rows per prefix partial slot
+  const size_t nps = (size_t)ds.P * ds.Hkv * NH + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
   size_t o = 0;
   L.cum = o; o = align256(o + (ds.P + B + 1) * 4);
@@ -688,18 +698,20 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
   P.c = ds.scale * 1.4426950408889634f;
 
-  // 16-row query blocks per wavefront (NT) and wavefronts per prefix tile (NRB, a power of two)
-  const int nt = P.R > 16 * WG_WAVES ? 2 : 1;
+  // row halves of the KV group, and wavefronts per prefix tile (NRB 16-row blocks, a power of two)
+  P.NH = P.R > 16 * WG_WAVES ? 2 : 1;
+  P.HkvP = P.Hkv * P.NH;
+  P.RS = P.NH == 2 ? 16 * WG_WAVES : P.R;
   int nrb = 1;
-  while (16 * nt * nrb < P.R) nrb *= 2;
+  while (16 * nrb < P.RS) nrb *= 2;
   P.table = ds.block_table; P.active = ds.seq_active;
   P.page_shift = ds.page_shift; P.max_pages = ds.max_pages; P.n_pages = ds.n_pages;
   const bool ext = ds.block_table != nullptr || ds.seq_active != nullptr;
   typedef void (*kern_t)(const SharedParams);
-  static const kern_t kerns[2][4] = {
-      {partial_kernel<1, 1, false>, partial_kernel<2, 1, false>, partial_kernel<4, 1, false>, partial_kernel<4, 2, false>},
-      {partial_kernel<1, 1, true>, partial_kernel<2, 1, true>, partial_kernel<4, 1, true>, partial_kernel<4, 2, true>}};
-  const kern_t kern = kerns[ext][nt == 2 ? 3 : nrb == 1 ? 0 : nrb == 2 ? 1 : 2];
+  static const kern_t kerns[2][3] = {
+      {partial_kernel<1, 1, false>, partial_kernel<2, 1, false>, partial_kernel<4, 1, false>},
+      {partial_kernel<1, 1, true>, partial_kernel<2, 1, true>, partial_kernel<4, 1, true>}};
+  const kern_t kern = kerns[ext][nrb == 1 ? 0 : nrb == 2 ? 1 : 2];
   // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
   {
     static std::mutex mu;
@@ -709,8 +721,8 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (int i = 0; i < 8; ++i) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i / 4][i % 4]),
+      for (int i = 0; i < 6; ++i) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i / 3][i % 3]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }

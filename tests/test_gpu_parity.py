@@ -82,6 +82,10 @@ CASES = [
     (1, 2, 32, 2, 128, 40, 33, "bf16"),       # r = 16
     (2, 4, 8, 2, 64, 77, 91, "bf16"),         # d = 64 bf16
     (5, 7, 6, 3, 128, 31, 1, "bf16"),         # one-row suffix buffers
+    (2, 10, 16, 2, 128, 140, 90, "bf16"),     # R = 80: a full row half and one of a single 16-row block
+    (3, 9, 14, 2, 128, 75, 120, "bf16"),      # r = 7, R = 63 / and next line R = 65: one row in the second half
+    (2, 13, 10, 2, 128, 100, 64, "bf16"),     # r = 5, R = 65
+    (2, 8, 32, 2, 128, 260, 70, "bf16"),      # r = 16, R = 128 with long prefixes
 ]
 
 

@@ -12,36 +12,38 @@ from paper_2512_21450_amd import workloads as wl
 TK = 32
 _f = B._lib.rl_decode_attn_debug_partition
 _f.restype = ctypes.c_int64
-_f.argtypes = [ctypes.c_int32] * 5 + [ctypes.c_void_p] * 2 + [ctypes.c_void_p, ctypes.c_int64,
+_f.argtypes = [ctypes.c_int32] * 6 + [ctypes.c_void_p] * 2 + [ctypes.c_void_p, ctypes.c_int64,
                                                                ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
 
 
-def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
+def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
     plens = np.ascontiguousarray(plens, np.int32)
     slens = np.ascontiguousarray(slens, np.int32)
-    cap = 4 * (P * (G + 1) * Hkv + 8 * 512) + 16
+    cap = 4 * (P * (G + 2) * Hkv + 8 * 512) + 16
     runs = np.zeros((cap, 8), np.int32)
     parts = np.zeros((cap, 6), np.int32)
     npart = ctypes.c_int64(0)
-    nr = _f(P, G, Hkv, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
+    nr = _f(P, G, Hkv, R, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
             parts.ctypes.data, cap, ctypes.byref(npart))
     assert 0 <= nr <= cap and npart.value <= cap
     return runs[:nr], parts[:npart.value]
 
 
-def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
-    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens)
+def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
+    """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half)."""
+    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R)
+    HkvP = Hkv * (2 if R > 64 else 1)
     tp = -(-np.clip(plens, 0, Lp_cap) // TK)
     ts = -(-np.clip(slens, 0, Ls_cap) // TK)
     # coverage: each unit's tiles [0, T) are tiled by its runs without gap or overlap
-    for kind, counts in ((0, tp), (1, ts)):
+    for kind, counts, heads in ((0, tp, HkvP), (1, ts, Hkv)):
         rk = runs[runs[:, 0] == kind]
         seen = {}
         for _, major, j, t0, n, w, v, slot in rk:
             assert n > 0
             seen.setdefault((major, j), []).append((t0, n))
         for major, T in enumerate(counts):
-            for j in range(Hkv):
+            for j in range(heads):
                 segs = sorted(seen.pop((major, j), []))
                 pos = 0
                 for t0, n in segs:
@@ -50,7 +52,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
                 assert pos == T, (kind, major, j, segs, T)
         assert not seen
     # slots: unique per kind, inside the workspace the library sizes
-    for kind, nslots in ((0, P * Hkv + 512), (1, P * G * Hkv + 8 * 256)):
+    for kind, nslots in ((0, P * HkvP + 512), (1, P * G * Hkv + 8 * 256)):
         sl = runs[runs[:, 0] == kind][:, 7]
         assert len(set(sl.tolist())) == len(sl)
         assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
@@ -60,7 +62,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens):
     assert key_r == key_p
     # balance: the two workgroups of a pair (w and 256 + w share a compute unit) together hold
     # an equal share of the prefix tiles and of the suffix tiles, up to rounding
-    npt, nst = int(tp.sum()) * Hkv, int(ts.sum()) * Hkv
+    npt, nst = int(tp.sum()) * HkvP, int(ts.sum()) * Hkv
     for kind, total in ((0, npt), (1, nst)):
         load = np.zeros(256, np.int64)
         rk = runs[runs[:, 0] == kind]
@@ -92,8 +94,10 @@ def test_partition_of_the_benchmark_workloads(name):
     rng = np.random.default_rng(w.seed)
     pl = wl._draw_lens(rng, w.prefix, w.P, w.Lp_cap)
     sl = wl._draw_lens(rng, w.suffix, w.B, w.Ls_cap)
-    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl)
+    runs = check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl, R=w.G * w.Hq // w.Hkv)
     assert len(runs) > 0
+    if name == "highbatch":                       # 128 rows per KV group: twice the prefix units
+        assert runs[runs[:, 0] == 0][:, 2].max() == 2 * w.Hkv - 1
 
 
 def test_prefix_heavy_batches_put_prefix_tiles_on_both_workgroups():
@@ -131,4 +135,4 @@ def test_partition_edge_cases():
         Lp_cap, Ls_cap = int(rng.integers(0, 3000)), int(rng.integers(0, 5000))
         pl = rng.integers(0, Lp_cap + 1, P) * (rng.random(P) < 0.8)
         sl = rng.integers(0, Ls_cap + 1, P * G) * (rng.random(P * G) < 0.7)
-        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl)
+        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128])))
