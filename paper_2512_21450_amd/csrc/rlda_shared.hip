@@ -5,7 +5,8 @@
 //                   wavefronts per compute unit.  Prefix tiles (the prompt s_0 shared by the K
 //                   sampled trajectories of a group, Algorithm 1 / Sec. 3.2.2 of the paper) are
 //                   staged once in LDS per workgroup and used by all G * Hq/Hkv query rows of
-//                   the KV group; suffix tiles (each trajectory's own generated tokens, Sec. 3.1
+//                   the KV group (by each half of them when there are more than 64: a wavefront
+//                   carries one 16-row block); suffix tiles (each trajectory's own generated tokens, Sec. 3.1
 //                   transition s' = (s, a)) are streamed by single wavefronts.  Every maximal
 //                   run of tiles of one (prompt or sequence, KV head) yields a partial (o, lse).
 //   combine_kernel  merges the partials of every (sequence, head) by log-sum-exp and writes
@@ -288,7 +289,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   auto head_of = [&](const Cur& c) { return c.j >> (P.NH - 1); };
   char* mine = lds + wv * STAGE_B;
 
-  constexpr bool QPRE = NT == 1;                            // NT = 2 has no registers left for a query prefetch
+  constexpr bool QPRE = NT == 1;                            // query rows of the next unit are prefetched (one block per wavefront)
   u32x4 rk[8], rv[8], qn[QPRE ? NT : 1][4];
   bf16x8 qf[NT][4];
   WaveState<NT> st;
