@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "7cf868db1bdb03fb653c70e65e289a346d02507e6fbb201aac2cdd1d62b037b0",
-    "fetch_bytes": 623879017,
-    "write_bytes": 18228531,
+    "csrc_sha256": "46d43e6706935ff521d3f58868a498b9e88d2110b46378a8801fd53362181bfb",
+    "fetch_bytes": 623853303,
+    "write_bytes": 18228768,
 }
 
 
