@@ -79,7 +79,7 @@ def main():
     ap.add_argument("--no-ref", action="store_true", help="token_logprob: no reference logits (no KL)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build is a single-GPU kernel library; only --gpus 1 is supported "
+        print("bench.py: this is a single-GPU kernel library; only --gpus 1 is supported "
               "(the path shards by prompt group with no exchange, nothing to measure across GPUs here)",
               file=sys.stderr)
         sys.exit(2)
