@@ -339,3 +339,18 @@ def test_two_level_shared_prefix_by_composition(B):
     out, lse = B.rl_lse_combine(parts_o, parts_l)
     torch.cuda.synchronize()
     util.compare(out.reshape(P * G, Hq, d), lse.reshape(P * G, Hq), ro, rl, "bf16", "two-level prefix")
+
+
+@pytest.mark.parametrize("P,plan", [(3000, "shared"), (3300, "simple")])
+def test_many_short_sequences_fill_the_length_scan(B, P, plan):
+    """Thousands of prompts and sequences: the in-kernel length scan and the owner search run at (and,
+    for the second case, beyond) their capacity, where the call falls back to the simple kernel."""
+    import torch
+    G, Hq, Hkv, d = 4, 4, 2, 128
+    x = util.random_case(70 + P, P, G, Hq, Hkv, d, 40, 40, "bf16")
+    t = util.to_device(x)
+    out = torch.empty((P * G, Hq, d), dtype=torch.float32, device="cuda:0")
+    ds = B.desc_from_tensors(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_suffix"], t["v_suffix"],
+                             t["suffix_lens"], 0.1, G, out, None)
+    assert B.rl_decode_attn_plan(ds) == {"shared": B.RLDA_ALGO_SHARED, "simple": B.RLDA_ALGO_SIMPLE}[plan]
+    check(x, 0.1, G, "bf16", "auto", f"P={P}", B)
