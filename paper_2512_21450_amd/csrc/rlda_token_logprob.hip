@@ -168,9 +168,11 @@ __global__ void __launch_bounds__(NT) token_partial_kernel(const Params P) {
     u32x4 ra[UNR], rb[UNR];
 #pragma unroll
     for (int k = 0; k < UNR; ++k) {
-      const int vk = min(v + k * NT, v1 - 1);                // past the end: re-read the last vector, not used
-      ra[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(za) + vk);
-      if (REF) rb[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(zb) + vk);
+      const int vk = v + k * NT;
+      if (vk < v1) {                                        // past the end: no load, the slot is not used
+        ra[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(za) + vk);
+        if (REF) rb[k] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(zb) + vk);
+      }
     }
 #pragma unroll
     for (int k = 0; k < UNR; ++k) {
