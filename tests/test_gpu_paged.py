@@ -158,3 +158,20 @@ def test_decode_loop_captured_in_a_graph(B):
         for i in range(steps):
             assert torch.equal(outs[i], eager[i][0]) and torch.equal(lses[i], eager[i][1]), f"replay {rep} step {i}"
         assert torch.equal(t["suffix_lens"], lens0 + steps * inc)
+
+
+def test_no_suffix_pages_at_all_and_very_large_pages(B):
+    import torch
+    x = util.random_case(9, 2, 4, 28, 4, 128, 130, 64, "bf16")
+    t = util.to_device(x)
+    # a batch right after the prompt: no page allocated yet, table with zero columns, empty pools
+    empty_pool = torch.empty((0, 4, 64, 128), dtype=torch.bfloat16, device="cuda")
+    table = torch.empty((8, 0), dtype=torch.int32, device="cuda")
+    out, lse = B.rl_decode_attn_paged(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], empty_pool, empty_pool,
+                                      table, t["suffix_lens"], 0.1, 4)
+    z = dict(x); z["suffix_lens"] = np.zeros(8, np.int32)
+    ro, rl = util.oracle(z, 0.1, 4)
+    util.compare(out, lse, ro, rl, "bf16", "no pages")
+    # one page of 1024 rows per sequence
+    y = wl.to_pages(util.random_case(10, 2, 4, 28, 4, 128, 130, 900, "bf16"), 1024, seed=1)
+    check(y, "bf16", 0.1, 4, what="page 1024")
