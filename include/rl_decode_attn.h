@@ -216,9 +216,10 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
 /*
  * Testing hook, pure host code: the static work partition the shared-prefix
  * path uses for the given lengths (HOST arrays prefix_lens [P], suffix_lens
- * [P*G]; rows_per_kv_group = G * Hq / Hkv).  When a KV group has more than 64
- * query rows its prefix units are (prompt, KV head, row half) and the "KV head"
- * column of a prefix row holds 2 * head + half.  `runs` receives one row of 8 int32 per run of tiles a workgroup
+ * [P*G]; rows_per_kv_group = G * Hq / Hkv, at most 256).  A KV group with more
+ * than 64 query rows is handled in n = 2 (or, above 128 rows, 4) row parts: its
+ * prefix units are (prompt, KV head, part) and the "KV head" column of a prefix
+ * row holds n * head + part.  `runs` receives one row of 8 int32 per run of tiles a workgroup
  * (prefix) or wavefront (suffix) processes: kind (0 prefix, 1 suffix), prompt
  * or sequence, KV head, first tile, tile count, workgroup, wavefront (-1 for
  * prefix), partial slot.  `parts` receives one row of 6 int32 per partial the

@@ -171,7 +171,8 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
   if (P < 0 || G < 0 || Hkv <= 0 || rows_per_kv_group <= 0 || !prefix_lens || !suffix_lens || !n_parts)
     return RLDA_ERR_INVALID;
   const int B = P * G;
-  const int HkvP = Hkv * (rows_per_kv_group > 16 * WG_WAVES ? 2 : 1);   // prefix units per prompt: (KV head, row half)
+  if (rows_per_kv_group > MAX_GROUP_ROWS) return RLDA_ERR_INVALID;
+  const int HkvP = Hkv * row_parts(rows_per_kv_group);                  // prefix units per prompt: (KV head, row part)
   std::vector<int> X(P + B + 2, 0);
   auto tp = [&](int p) { return ceil_div(clampi(prefix_lens[p], 0, Lp_cap), TK); };
   auto ts = [&](int b) { return ceil_div(clampi(suffix_lens[b], 0, Ls_cap), TK); };

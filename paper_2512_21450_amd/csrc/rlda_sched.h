@@ -47,6 +47,11 @@ struct Sched {
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// The R = G * Hq/Hkv query rows that share a prefix tile are handled in row parts of at most 64
+// rows (one 16-row block per wavefront): 1, 2 or 4 parts.
+constexpr int MAX_GROUP_ROWS = 256;
+__host__ __device__ inline int row_parts(int R) { return R > 128 ? 4 : (R > 64 ? 2 : 1); }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {

@@ -53,11 +53,11 @@ struct SharedParams {
   float* po; float* pl;   // prefix partials [slot][RS][D], [slot][RS]
   float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
-  // The R = G * r query rows of a KV group are handled as NH row halves of at most 64 rows (NH = 2
-  // when R > 64): a prefix unit is (prompt, KV head, half), numbered jp = j * NH + half, so that a
-  // wavefront never carries more than one 16-row block.  HkvP = Hkv * NH units per prompt; a prefix
-  // partial slot holds RS rows.
-  int NH, HkvP, RS;
+  // The R = G * r query rows of a KV group are handled in NH = 1, 2 or 4 row parts of at most 64
+  // rows (NH = 2^NHs, more than one when R > 64): a prefix unit is (prompt, KV head, part), numbered
+  // jp = j * NH + part, so that a wavefront never carries more than one 16-row block.
+  // HkvP = Hkv * NH units per prompt; a prefix partial slot holds RS rows.
+  int NH, NHs, HkvP, RS;
   float c;                // scale * log2(e): scores are kept in base 2
   // extended form only (kernels instantiated with EXT = true):
   const int32_t* table;   // [B, max_pages] page ids when ks / vs are page pools [n_pages, Hkv, page, D], else null
@@ -288,7 +288,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int rowbase = 16 * NT * rb;                         // inside the unit's row half
   const int lrow = lane >> 4, chunk = lane & 15;
   auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
-  auto head_of = [&](const Cur& c) { return c.j >> (P.NH - 1); };
+  auto head_of = [&](const Cur& c) { return c.j >> P.NHs; };
   char* mine = lds + wv * STAGE_B;
 
   constexpr bool QPRE = NT == 1;                            // query rows of the next unit are prefetched (one block per wavefront)
@@ -583,7 +583,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int cumP = X[P.P];
   const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
-  const int half = P.NH == 2 ? grow >> 6 : 0;
+  const int half = P.NH > 1 ? grow >> 6 : 0;
   const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
 
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -656,7 +656,7 @@ struct Layout { size_t cum, pl, po, sl, so, total; };
 
 Layout layout(const Problem& ds) {
   const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, Rg = r * ds.G;
-  const size_t NH = Rg > 64 ? 2 : 1, R = NH == 2 ? 64 : Rg;   // rows per prefix partial slot
+  const size_t NH = row_parts((int)Rg), R = NH > 1 ? 64 : Rg;   // rows per prefix partial slot
   const size_t nps = (size_t)ds.P * ds.Hkv * NH + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
   size_t o = 0;
@@ -675,7 +675,7 @@ bool shared_supported(const Problem& ds) {
   if (ds.dtype != RLDA_BF16 || ds.d != D) return false;
   const int64_t B = (int64_t)ds.P * ds.G;
   const int r = ds.Hq / ds.Hkv;
-  if (r > 16 || (int64_t)r * ds.G > 128) return false;                  // rows of one KV group: <= 8 MFMA row blocks
+  if (r > 16 || (int64_t)r * ds.G > MAX_GROUP_ROWS) return false;       // rows of one KV group: <= 4 parts of 64
   if (ds.P + B + 1 > MAX_SCAN) return false;                            // the length scan lives in LDS
   if ((int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) > MAX_LINE ||
       B * ds.Hkv * ceil_div(ds.Ls_cap, TK) > MAX_LINE) return false;       // 32-bit tile arithmetic
@@ -702,9 +702,10 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   P.c = ds.scale * 1.4426950408889634f;
 
   // row halves of the KV group, and wavefronts per prefix tile (NRB 16-row blocks, a power of two)
-  P.NH = P.R > 16 * WG_WAVES ? 2 : 1;
+  P.NH = row_parts(P.R);
+  P.NHs = P.NH == 4 ? 2 : P.NH - 1;
   P.HkvP = P.Hkv * P.NH;
-  P.RS = P.NH == 2 ? 16 * WG_WAVES : P.R;
+  P.RS = P.NH > 1 ? 16 * WG_WAVES : P.R;
   int nrb = 1;
   while (16 * nrb < P.RS) nrb *= 2;
   P.table = ds.block_table; P.active = ds.seq_active;

@@ -86,6 +86,9 @@ CASES = [
     (3, 9, 14, 2, 128, 75, 120, "bf16"),      # r = 7, R = 63 / and next line R = 65: one row in the second half
     (2, 13, 10, 2, 128, 100, 64, "bf16"),     # r = 5, R = 65
     (2, 8, 32, 2, 128, 260, 70, "bf16"),      # r = 16, R = 128 with long prefixes
+    (2, 32, 14, 2, 128, 150, 60, "bf16"),     # G = 32, r = 7: R = 224, four row parts (the last one short)
+    (1, 16, 32, 2, 128, 100, 40, "bf16"),     # r = 16, R = 256
+    (2, 17, 16, 2, 128, 70, 33, "bf16"),      # R = 136: three of four parts used
 ]
 
 

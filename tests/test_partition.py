@@ -32,7 +32,7 @@ def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
 def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
     """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half)."""
     runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R)
-    HkvP = Hkv * (2 if R > 64 else 1)
+    HkvP = Hkv * (4 if R > 128 else 2 if R > 64 else 1)
     tp = -(-np.clip(plens, 0, Lp_cap) // TK)
     ts = -(-np.clip(slens, 0, Ls_cap) // TK)
     # coverage: each unit's tiles [0, T) are tiled by its runs without gap or overlap
@@ -135,4 +135,4 @@ def test_partition_edge_cases():
         Lp_cap, Ls_cap = int(rng.integers(0, 3000)), int(rng.integers(0, 5000))
         pl = rng.integers(0, Lp_cap + 1, P) * (rng.random(P) < 0.8)
         sl = rng.integers(0, Ls_cap + 1, P * G) * (rng.random(P * G) < 0.7)
-        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128])))
+        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128, 129, 256])))
