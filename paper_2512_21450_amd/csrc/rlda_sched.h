@@ -36,7 +36,12 @@ constexpr int WG_WAVES = 4;       // wavefronts per workgroup
 constexpr int N_CU = 256;         // workgroup pairs: one per compute unit
 constexpr int N_WG = 2 * N_CU;    // workgroups of the partial kernel
 constexpr int PREFIX_WEIGHT = 6;  // cost of a prefix tile ...
-constexpr int SUFFIX_WEIGHT = 4;  // ... relative to a suffix tile
+constexpr int SUFFIX_WEIGHT = 4;  // ... relative to a suffix tile, when the batch saturates the memory system
+// A batch of fewer tiles than this (256 MB of K/V) does not: its suffix tiles then come back in half the
+// time while a prefix tile still takes a workgroup one memory round trip per group of four plus the
+// matrix work of all row blocks, so prefix tiles weigh more.
+constexpr int SMALL_BATCH_TILES = 16384;
+constexpr int PREFIX_WEIGHT_SMALL = 14;
 
 struct Sched {
   int NPT;      // prefix tiles in total (all units)
@@ -54,10 +59,12 @@ constexpr int MAX_GROUP_ROWS = 256;
 __host__ __device__ inline int row_parts(int R) { return R > 128 ? 4 : (R > 64 ? 2 : 1); }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
+// wP is the weight for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead
 __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {
   Sched s;
-  s.NPT = NPT; s.NST = NST; s.wP = wP; s.wS = wS; s.n_cu = n_cu;
+  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_cu = n_cu;
   s.heavy = wP * NPT > wS * NST;               // lines are at most MAX_LINE tiles: no overflow
+  s.wP = !s.heavy && NPT + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : wP;
   return s;
 }
 

@@ -71,7 +71,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
         assert load.max() <= -(-total // 256) and load.min() >= total // 256
     # inside a pair the heavier line is shared: the second workgroup has prefix tiles only if the first
     # has no suffix tiles, and the two then differ by less than two tiles' weight
-    WP, WS = 6, 4
+    WP, WS = (14 if npt + nst < 16384 and 6 * npt <= 4 * nst else 6), 4   # small suffix-heavy batches weigh prefix tiles more
     wa, wb = np.zeros(256, np.int64), np.zeros(256, np.int64)
     a_suffix, b_prefix = np.zeros(256, np.int64), np.zeros(256, np.int64)
     for kind, _, _, _, n, w, _, _ in runs:
