@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "4b3eadb95672f3b768ca6fced55d176258d90f52c16b49a17857a5647a0f4a43",
-    "fetch_bytes": 623855025,
-    "write_bytes": 18228396,
+    "csrc_sha256": "83045e9a48663b84001e17d029fcf4189b1f0a90e061e8be73e31a0f772b4864",
+    "fetch_bytes": 623853214,
+    "write_bytes": 18228100,
 }
 
 
