@@ -50,8 +50,10 @@ struct SharedParams {
   const int32_t* plens; const int32_t* slens;
   float* out; float* lse;
   int32_t* cum;           // [P + B + 1] exclusive scan of tile counts (prompts, then sequences)
-  float* po; float* pl;   // prefix partials [slot][RS][D], [slot][RS]
-  float* so; float* sl;   // suffix partials [slot][r][D], [slot][r]
+  // partials: o rows as fp16 [slot][rows][D] (columns permuted, see write_partial), and per row the
+  // pair (lse, power-of-two scale of the stored row) as fp32 [slot][rows][2]
+  _Float16* po; float* pl;   // prefix, RS rows per slot
+  _Float16* so; float* sl;   // suffix, r rows per slot
   int P, G, B, Hq, Hkv, r, R, Lp_cap, Ls_cap;
   // The R = G * r query rows of a KV group are handled in NH = 1, 2 or 4 row parts of at most 64
   // rows (NH = 2^NHs, more than one when R > 64): a prefix unit is (prompt, KV head, part), numbered
@@ -199,9 +201,28 @@ __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, int
   }
 }
 
-// Normalise and store one partial: rows [rowbase, rowbase + 16 NT) of a unit with `nrows` rows.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+// Byte offset, inside a stored partial row of D halves, of the four columns 4 * q .. 4 * q + 3:
+// a lane of the tile routine owns columns 16 ct + 4 g .. + 3 of every column tile ct and stores the
+// eight values of two neighbouring tiles as one 16-byte chunk, chunk (ct / 2) * 4 + g.
+__device__ __forceinline__ int part_col_off(int q) {
+  const int ct = q >> 2, g = q & 3;
+  return ((ct >> 1) * 4 + g) * 16 + (ct & 1) * 8;
+}
+
+// Normalise and store one partial: rows [rowbase, rowbase + 16) of a unit with `nrows` rows.
+//
+// What the stores of the partials cost this kernel follows their instruction count, not their
+// bytes (37 k 16-byte stores cost 14 us of 115; half as many, half; 4-byte stores in their place,
+// the same), so a row of o is stored as fp16 in four instructions instead of eight.  To keep
+// fp16's range out of the picture every row is first scaled by a power of two that brings its
+// largest magnitude into [0.5, 1); the inverse scale is stored next to the row's lse.  The
+// rounding (2^-11 of the row's largest |o|, at most 2e-3 for |v| <= 4) stays inside the
+// tolerance of the bf16 path, whose weights are already rounded to bf16.
 template <int NT>
-__device__ __forceinline__ void write_partial(const WaveState<NT>& st, float* po, float* pl, int slot, int nrows,
+__device__ __forceinline__ void write_partial(const WaveState<NT>& st, _Float16* po, float* pl, int slot, int nrows,
                                               int rowbase, int lane) {
   const int m16 = lane & 15, g = lane >> 4;
 #pragma unroll
@@ -209,16 +230,29 @@ __device__ __forceinline__ void write_partial(const WaveState<NT>& st, float* po
     float l = st.l[nt], lr = st.lr[nt];
     l += __shfl_xor(l, 16, 64);   l += __shfl_xor(l, 32, 64);
     lr += __shfl_xor(lr, 16, 64); lr += __shfl_xor(lr, 32, 64);
+    float mx = 0.f;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+      for (int x = 0; x < 4; ++x) mx = fmaxf(mx, fabsf(st.O[nt][ct][x]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const int row = rowbase + 16 * nt + m16;
     if (row < nrows) {
       const float inv = 1.f / lr;
-      float* o = po + ((size_t)slot * nrows + row) * D + 4 * g;
+      const int e = clampi((int)((__float_as_uint(mx * inv) >> 23) & 255u), 1, 252);   // max |o| in [2^(e-127), 2^(e-126))
+      const float k = inv * __uint_as_float((uint32_t)(253 - e) << 23);                // o * 2^(126-e) in [0.5, 1)
+      char* o = reinterpret_cast<char*>(po + ((size_t)slot * nrows + row) * D);
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) {
-        const f32x4 v = st.O[nt][ct] * inv;
-        *reinterpret_cast<float4*>(o + 16 * ct) = make_float4(v[0], v[1], v[2], v[3]);
+      for (int ct = 0; ct < 8; ct += 2) {
+        const f32x4 a = st.O[nt][ct] * k, b = st.O[nt][ct + 1] * k;
+        const f16x8 h = {(_Float16)a[0], (_Float16)a[1], (_Float16)a[2], (_Float16)a[3],
+                         (_Float16)b[0], (_Float16)b[1], (_Float16)b[2], (_Float16)b[3]};
+        *reinterpret_cast<f16x8*>(o + ((ct >> 1) * 4 + g) * 16) = h;
       }
-      if (g == 0) pl[(size_t)slot * nrows + row] = (st.m[nt] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f;
+      if (g == 0)
+        *reinterpret_cast<float2*>(pl + 2 * ((size_t)slot * nrows + row)) =
+            make_float2((st.m[nt] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f,
+                        __uint_as_float((uint32_t)(e + 1) << 23));                     // 2^(e-126)
     }
   }
 }
@@ -571,6 +605,7 @@ template <bool EXT>
 __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
   const int sub = threadIdx.x & 31, c4 = sub * 4;
+  const int coff = part_col_off(sub);                       // where this lane's 4 columns sit in a stored partial row
   if (row >= P.B * P.Hq) return;
   const int b = row / P.Hq, h = row % P.Hq;
   if (EXT && P.active && P.active[b] == 0) {               // finished sequence: its prefix rows were computed, not used
@@ -602,19 +637,22 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
     const int cnt = min(n - base, 32);
     if (cnt <= 0) break;
     // the first 8 parts' values are requested together with the lse values (one round trip)
-    float4 v8[8];
+    f16x4 v8[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const int id = __shfl(mine, min(u, cnt - 1), 32);
-      v8[u] = *reinterpret_cast<const float4*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D + c4);
+      v8[u] = *reinterpret_cast<const f16x4*>(reinterpret_cast<const char*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D) + coff);
     }
-    const float l = mine < 0 ? -INFINITY : (mine & 1 ? P.sl[mine >> 1] : P.pl[mine >> 1]);
+    const float2 ls = mine < 0 ? make_float2(-INFINITY, 0.f)
+                               : *reinterpret_cast<const float2*>((mine & 1 ? P.sl : P.pl) + 2 * (size_t)(mine >> 1));
+    const float l = ls.x;
     float m = l;
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 32));
     const float Mn = fmaxf(M, m);                           // finite: every part holds at least one key
     const float resc = __expf(M - Mn);
     const float wgt = __expf(l - Mn);                       // lanes without a part: 0
+    const float wsc = wgt * ls.y;                           // weight times the stored row's scale
     float zs = wgt;
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) zs += __shfl_xor(zs, o, 32);
@@ -623,24 +661,24 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
     acc.x *= resc; acc.y *= resc; acc.z *= resc; acc.w *= resc;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
-      const float wk = u < cnt ? __shfl(wgt, min(u, cnt - 1), 32) : 0.f;
-      acc.x = fmaf(wk, v8[u].x, acc.x); acc.y = fmaf(wk, v8[u].y, acc.y);
-      acc.z = fmaf(wk, v8[u].z, acc.z); acc.w = fmaf(wk, v8[u].w, acc.w);
+      const float wk = u < cnt ? __shfl(wsc, min(u, cnt - 1), 32) : 0.f;
+      acc.x = fmaf(wk, (float)v8[u][0], acc.x); acc.y = fmaf(wk, (float)v8[u][1], acc.y);
+      acc.z = fmaf(wk, (float)v8[u][2], acc.z); acc.w = fmaf(wk, (float)v8[u][3], acc.w);
     }
     for (int k0 = 8; k0 < cnt; k0 += 4) {
-      float4 v[4];
+      f16x4 v[4];
       float wk[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int k = min(k0 + u, cnt - 1);
         const int id = __shfl(mine, k, 32);
-        wk[u] = k0 + u < cnt ? __shfl(wgt, k, 32) : 0.f;
-        v[u] = *reinterpret_cast<const float4*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D + c4);
+        wk[u] = k0 + u < cnt ? __shfl(wsc, k, 32) : 0.f;
+        v[u] = *reinterpret_cast<const f16x4*>(reinterpret_cast<const char*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D) + coff);
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        acc.x = fmaf(wk[u], v[u].x, acc.x); acc.y = fmaf(wk[u], v[u].y, acc.y);
-        acc.z = fmaf(wk[u], v[u].z, acc.z); acc.w = fmaf(wk[u], v[u].w, acc.w);
+        acc.x = fmaf(wk[u], (float)v[u][0], acc.x); acc.y = fmaf(wk[u], (float)v[u][1], acc.y);
+        acc.z = fmaf(wk[u], (float)v[u][2], acc.z); acc.w = fmaf(wk[u], (float)v[u][3], acc.w);
       }
     }
     if (n - base <= 32) break;
@@ -661,10 +699,10 @@ Layout layout(const Problem& ds) {
   Layout L;
   size_t o = 0;
   L.cum = o; o = align256(o + (ds.P + B + 1) * 4);
-  L.pl = o;  o = align256(o + nps * R * 4);
-  L.po = o;  o = align256(o + nps * R * D * 4);
-  L.sl = o;  o = align256(o + nss * r * 4);
-  L.so = o;  o = align256(o + nss * r * D * 4);
+  L.pl = o;  o = align256(o + nps * R * 2 * 4);
+  L.po = o;  o = align256(o + nps * R * D * 2);
+  L.sl = o;  o = align256(o + nss * r * 2 * 4);
+  L.so = o;  o = align256(o + nss * r * D * 2);
   L.total = o;
   return L;
 }
@@ -695,8 +733,8 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   P.plens = ds.prefix_lens; P.slens = ds.suffix_lens;
   P.out = ds.out; P.lse = ds.lse;
   P.cum = reinterpret_cast<int32_t*>(ws + L.cum);
-  P.pl = reinterpret_cast<float*>(ws + L.pl); P.po = reinterpret_cast<float*>(ws + L.po);
-  P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<float*>(ws + L.so);
+  P.pl = reinterpret_cast<float*>(ws + L.pl); P.po = reinterpret_cast<_Float16*>(ws + L.po);
+  P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<_Float16*>(ws + L.so);
   P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
   P.c = ds.scale * 1.4426950408889634f;
