@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "83045e9a48663b84001e17d029fcf4189b1f0a90e061e8be73e31a0f772b4864",
-    "fetch_bytes": 623853214,
-    "write_bytes": 18228100,
+    "csrc_sha256": "7a8d71008b417924e570daa70443f179dd4ff5aac58fa3edbfbf8624164f8772",
+    "fetch_bytes": 623715708,
+    "write_bytes": 9339956,
 }
 
 
