@@ -66,6 +66,8 @@ def main():
     ap.add_argument("--event-every", type=int, default=8, help="record per-kernel HIP events on every n-th step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
+    ap.add_argument("--naive-steps", type=int, default=20,
+                    help="steps of the unoptimised GPU kernel timed as a reference row (0 = skip)")
     ap.add_argument("--page-size", type=int, default=0,
                     help="0: contiguous suffix store (the headline configuration); else rows per page of a paged store")
     ap.add_argument("--finished", type=float, default=0.0,
@@ -221,6 +223,39 @@ def main():
                "sample": f"{n} of {w.B} sequences (all {w.Hq} heads, evenly spaced, contiguous layout), "
                          f"{passes} passes, {c1 - c0:.2f} s"}
 
+        # the same oracle on one thread, on every 16th sequence of the sample
+        s1 = seqs[::16]
+        r1 = np.stack([np.repeat(s1, w.Hq), np.tile(np.arange(w.Hq, dtype=np.int32), len(s1))], 1)
+        c0 = time.perf_counter()
+        ref.decode_attn_ref(x0["q"], x0["k_prefix"], x0["v_prefix"], x0["prefix_lens"], x0["k_suffix"],
+                            x0["v_suffix"], x0["suffix_lens"], w.scale, w.G, rows=r1, n_threads=1)
+        cpu["one_thread_value"] = len(s1) / (time.perf_counter() - c0)
+        cpu["one_thread_sample"] = f"{len(s1)} sequences, one pass"
+
+    # second reference row: the unoptimised GPU kernel (one wavefront per row, no sharing, no split)
+    naive = None
+    if plan == 2 and not paged and args.naive_steps > 0:
+        dn = descs[0]
+        keep = dn.algo
+        dn.algo = B.RLDA_ALGO_SIMPLE
+        try:
+            def naive_step():
+                rc = B.rl_decode_attn_raw(dn, sh)
+                if rc != 0:
+                    raise B.RldaError(rc)
+            for _ in range(2):
+                naive_step()
+            torch.cuda.synchronize()
+            n0 = time.perf_counter()
+            for _ in range(args.naive_steps):
+                naive_step()
+            torch.cuda.synchronize()
+            nms = (time.perf_counter() - n0) * 1e3 / args.naive_steps
+        finally:
+            dn.algo = keep
+        naive = {"kernel": "simple_kernel", "ms_per_step": nms, "steps": args.naive_steps,
+                 "GBps": ab["total"] / (nms * 1e-3) / 1e9}
+
     kern_us = float(kern_ms.mean() * 1e3)
     achieved = ab["total"] / (kern_us * 1e-6) / 1e9
     res = {
@@ -245,6 +280,7 @@ def main():
                      "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),
                      "rest_of_step_us_mean": float(rest_ms.mean() * 1e3)},
         "cpu_baseline": cpu,
+        "naive_gpu_baseline": naive,
         "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
     }
     print(json.dumps(res))

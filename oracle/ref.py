@@ -46,6 +46,11 @@ def _load():
         lib.rl_decode_attn_ref_f64.restype = ip
         lib.rl_decode_attn_ref_f64.argtypes = [ip] * 8 + [ctypes.c_double] + [vp] * 9 + [
             vp, ctypes.c_int64, ip, ctypes.POINTER(ip)]
+        lib.rl_decode_attn_ref_kv8_f64.restype = ip
+        lib.rl_decode_attn_ref_kv8_f64.argtypes = [ip, vp, vp] + [ip] * 7 + [ctypes.c_double] + [vp] * 9 + [
+            vp, ctypes.c_int64, ip, ctypes.POINTER(ip)]
+        lib.rl_e4m3_to_f64_ref.restype = ctypes.c_double
+        lib.rl_e4m3_to_f64_ref.argtypes = [ctypes.c_uint8]
         lib.rl_lse_combine_ref_f64.restype = None
         lib.rl_lse_combine_ref_f64.argtypes = [ip, ip, vp, vp, vp, vp]
         _lib = lib
@@ -64,12 +69,22 @@ def _elem(a: np.ndarray) -> int:
     raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
 
 
+def e4m3_to_f64(bits) -> np.ndarray:
+    """Values of e4m3 bytes (any shape), by the C oracle's decoder."""
+    lib = _load()
+    b = np.asarray(bits, dtype=np.uint8)
+    return np.array([lib.rl_e4m3_to_f64_ref(int(x)) for x in b.ravel()], dtype=np.float64).reshape(b.shape)
+
+
 def decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens,
-                    scale, G, rows=None, n_threads=0, return_threads=False):
+                    scale, G, rows=None, n_threads=0, return_threads=False, k_scale=None, v_scale=None):
     """out[B,Hq,d], lse[B,Hq] in fp64.  Shapes as in rl_decode_attn_ref.h.
 
     ``rows``: optional int array [n,2] of (b, h) pairs; then only those entries
     are computed and the rest of the returned arrays is NaN.
+
+    K/V stores of dtype uint8 hold e4m3 bytes; ``k_scale`` / ``v_scale`` ([Hkv]
+    float32 or None) are then the per-KV-head dequantisation factors.
     """
     lib = _load()
     q = np.ascontiguousarray(q)
@@ -79,8 +94,15 @@ def decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suff
     Ls_cap = k_suffix.shape[2]
     assert B == P * G and k_suffix.shape[0] == B and k_suffix.shape[1] == Hkv
     arrs = [np.ascontiguousarray(a) for a in (k_prefix, v_prefix, k_suffix, v_suffix)]
+    kv8 = arrs[0].dtype == np.uint8
     for a in arrs:
-        assert _elem(a) == et
+        assert (a.dtype == np.uint8) if kv8 else (_elem(a) == et)
+    if not kv8:
+        assert k_scale is None and v_scale is None, "scales belong to e4m3 stores"
+    ksc = None if k_scale is None else np.ascontiguousarray(k_scale, dtype=np.float32)
+    vsc = None if v_scale is None else np.ascontiguousarray(v_scale, dtype=np.float32)
+    assert ksc is None or ksc.shape == (Hkv,)
+    assert vsc is None or vsc.shape == (Hkv,)
     pl = np.ascontiguousarray(prefix_lens, dtype=np.int32)
     sl = np.ascontiguousarray(suffix_lens, dtype=np.int32)
     assert pl.shape == (P,) and sl.shape == (B,)
@@ -93,13 +115,15 @@ def decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suff
         r = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 2)
         n_rows = r.shape[0]
     used = ctypes.c_int(0)
-    rc = lib.rl_decode_attn_ref_f64(et, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale),
-                                    _ptr(q), _ptr(arrs[0]), _ptr(arrs[1]), _ptr(pl),
-                                    _ptr(arrs[2]), _ptr(arrs[3]), _ptr(sl),
-                                    _ptr(out), _ptr(lse), _ptr(r), n_rows,
-                                    int(n_threads), ctypes.byref(used))
+    tail = (P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale),
+            _ptr(q), _ptr(arrs[0]), _ptr(arrs[1]), _ptr(pl), _ptr(arrs[2]), _ptr(arrs[3]), _ptr(sl),
+            _ptr(out), _ptr(lse), _ptr(r), n_rows, int(n_threads), ctypes.byref(used))
+    if kv8:
+        rc = lib.rl_decode_attn_ref_kv8_f64(et, _ptr(ksc), _ptr(vsc), *tail)
+    else:
+        rc = lib.rl_decode_attn_ref_f64(et, *tail)
     if rc != 0:
-        raise ValueError(f"rl_decode_attn_ref_f64 returned {rc}")
+        raise ValueError(f"oracle returned {rc}")
     if return_threads:
         return out, lse, used.value
     return out, lse
@@ -136,7 +160,7 @@ def gather_pages(pages, block_table, suffix_lens, Ls_cap):
 
 
 def decode_attn_paged_ref(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
-                          seq_active, scale, G, rows=None, n_threads=0):
+                          seq_active, scale, G, rows=None, n_threads=0, k_scale=None, v_scale=None):
     """The paged-suffix call by its definition: gather every sequence's pages
     in table order and evaluate the attention of the contiguous layout;
     sequences marked finished (seq_active[b] == 0) get out = 0, lse = -inf."""
@@ -146,7 +170,7 @@ def decode_attn_paged_ref(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, 
     ks = gather_pages(k_pages, block_table, sl, cap)
     vs = gather_pages(v_pages, block_table, sl, cap)
     out, lse = decode_attn_ref(q, k_prefix, v_prefix, prefix_lens, ks, vs, sl, scale, G, rows=rows,
-                               n_threads=n_threads)
+                               n_threads=n_threads, k_scale=k_scale, v_scale=v_scale)
     if seq_active is not None:
         dead = np.asarray(seq_active) == 0
         out[dead] = 0.0

@@ -23,10 +23,28 @@ static double widen(const void* base, int elem_type, int64_t idx) {
   return (double)f;
 }
 
+/* One e4m3 byte (8-bit float of the OCP 8-bit floating point format: sign, 4 exponent bits with
+   bias 7, 3 mantissa bits; exponent 0 is subnormal, S.1111.111 is NaN, there is no infinity; the
+   largest finite magnitude is 448) to fp64, exactly. */
+static double e4m3_to_f64(uint8_t b) {
+  const int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+  double v;
+  if (e == 15 && m == 7) return NAN;
+  if (e == 0) v = ldexp((double)m, -9);              /* m/8 * 2^-6 */
+  else        v = ldexp((double)(8 + m), e - 10);    /* (1 + m/8) * 2^(e-7) */
+  return sign ? -v : v;
+}
+
+/* Element of a K or V store: as widen(), plus RLREF_E4M3 bytes. */
+static double widen_kv(const void* base, int kv_type, int64_t idx) {
+  if (kv_type == RLREF_E4M3) return e4m3_to_f64(((const uint8_t*)base)[idx]);
+  return widen(base, kv_type, idx);
+}
+
 static int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
 /* One (b, h): Sec. 3.1 state = prompt prefix then own generated tokens. */
-static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
+static void one_row(int elem_type, int kv_type, double kscale, double vscale, int G, int Hq, int Hkv, int d, int Lp_cap,
                     int Ls_cap, double scale, const void* q, const void* kp,
                     const void* vp, const int32_t* plens, const void* ks,
                     const void* vs, const int32_t* slens, int b, int h,
@@ -54,7 +72,7 @@ static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
     const void* kb = n < Lp ? kp : ks;
     const int64_t ko = n < Lp ? poff + (int64_t)n * d : soff + (int64_t)(n - Lp) * d;
     double acc = 0.0;
-    for (int c = 0; c < d; ++c) acc += widen(q, elem_type, qoff + c) * widen(kb, elem_type, ko + c);
+    for (int c = 0; c < d; ++c) acc += widen(q, elem_type, qoff + c) * (kscale * widen_kv(kb, kv_type, ko + c));
     s[n] = scale * acc;
   }
   double m = s[0];
@@ -66,19 +84,20 @@ static void one_row(int elem_type, int G, int Hq, int Hkv, int d, int Lp_cap,
     const void* vb = n < Lp ? vp : vs;
     const int64_t vo = n < Lp ? poff + (int64_t)n * d : soff + (int64_t)(n - Lp) * d;
     const double w = exp(s[n] - l);
-    for (int c = 0; c < d; ++c) acc[c] += w * widen(vb, elem_type, vo + c);
+    for (int c = 0; c < d; ++c) acc[c] += w * (vscale * widen_kv(vb, kv_type, vo + c));
   }
   for (int c = 0; c < d; ++c) out_row[c] = acc[c];
   if (lse_val) *lse_val = l;
 }
 
-int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
-                           int Lp_cap, int Ls_cap, double scale, const void* q,
-                           const void* k_prefix, const void* v_prefix,
-                           const int32_t* prefix_lens, const void* k_suffix,
-                           const void* v_suffix, const int32_t* suffix_lens,
-                           double* out, double* lse, const int32_t* rows,
-                           int64_t n_rows, int n_threads, int* threads_used) {
+static int attn_ref(int elem_type, int kv_type, const float* k_scale, const float* v_scale,
+                    int P, int G, int Hq, int Hkv, int d,
+                    int Lp_cap, int Ls_cap, double scale, const void* q,
+                    const void* k_prefix, const void* v_prefix,
+                    const int32_t* prefix_lens, const void* k_suffix,
+                    const void* v_suffix, const int32_t* suffix_lens,
+                    double* out, double* lse, const int32_t* rows,
+                    int64_t n_rows, int n_threads, int* threads_used) {
   if (elem_type != RLREF_F32 && elem_type != RLREF_BF16) return -1;
   if (P < 0 || G < 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || Lp_cap < 0 || Ls_cap < 0) return -1;
   if (Hq % Hkv != 0) return -1;
@@ -105,7 +124,9 @@ int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
     for (int64_t i = 0; i < total; ++i) {
       const int b = rows ? rows[2 * i] : (int)(i / Hq);
       const int h = rows ? rows[2 * i + 1] : (int)(i % Hq);
-      one_row(elem_type, G, Hq, Hkv, d, Lp_cap, Ls_cap, scale, q, k_prefix, v_prefix,
+      const int j = h / (Hq / Hkv);
+      one_row(elem_type, kv_type, k_scale ? (double)k_scale[j] : 1.0, v_scale ? (double)v_scale[j] : 1.0,
+              G, Hq, Hkv, d, Lp_cap, Ls_cap, scale, q, k_prefix, v_prefix,
               prefix_lens, k_suffix, v_suffix, suffix_lens, b, h,
               out + ((int64_t)b * Hq + h) * d, lse ? lse + (int64_t)b * Hq + h : NULL, s);
     }
@@ -114,6 +135,33 @@ int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
   if (threads_used) *threads_used = used;
   return 0;
 }
+
+int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
+                           int Lp_cap, int Ls_cap, double scale, const void* q,
+                           const void* k_prefix, const void* v_prefix,
+                           const int32_t* prefix_lens, const void* k_suffix,
+                           const void* v_suffix, const int32_t* suffix_lens,
+                           double* out, double* lse, const int32_t* rows,
+                           int64_t n_rows, int n_threads, int* threads_used) {
+  return attn_ref(elem_type, elem_type, NULL, NULL, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, scale, q, k_prefix,
+                  v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, out, lse, rows, n_rows, n_threads,
+                  threads_used);
+}
+
+int rl_decode_attn_ref_kv8_f64(int q_type, const float* k_scale, const float* v_scale,
+                               int P, int G, int Hq, int Hkv, int d,
+                               int Lp_cap, int Ls_cap, double scale, const void* q,
+                               const void* k_prefix, const void* v_prefix,
+                               const int32_t* prefix_lens, const void* k_suffix,
+                               const void* v_suffix, const int32_t* suffix_lens,
+                               double* out, double* lse, const int32_t* rows,
+                               int64_t n_rows, int n_threads, int* threads_used) {
+  return attn_ref(q_type, RLREF_E4M3, k_scale, v_scale, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, scale, q, k_prefix,
+                  v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, out, lse, rows, n_rows, n_threads,
+                  threads_used);
+}
+
+double rl_e4m3_to_f64_ref(uint8_t bits) { return e4m3_to_f64(bits); }
 
 void rl_lse_combine_ref_f64(int n, int d, const double* o_parts,
                             const double* lse_parts, double* out, double* lse) {

@@ -46,7 +46,7 @@
 extern "C" {
 #endif
 
-enum { RLREF_F32 = 0, RLREF_BF16 = 1 };
+enum { RLREF_F32 = 0, RLREF_BF16 = 1, RLREF_E4M3 = 2 };
 
 /*
  * All pointers are HOST pointers, contiguous row-major:
@@ -73,6 +73,34 @@ int rl_decode_attn_ref_f64(int elem_type, int P, int G, int Hq, int Hkv, int d,
                            double* out, double* lse,
                            const int32_t* rows, int64_t n_rows,
                            int n_threads, int* threads_used);
+
+/*
+ * The same attention when the K and V stores hold 8-bit floats (the e4m3 encoding of the OCP
+ * 8-bit floating point format: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits, subnormals,
+ * no infinity, S.1111.111 = NaN, largest finite value 448), one byte per element, with one
+ * dequantisation factor per KV head:
+ *   K_n[c] = k_scale[j] * e4m3(k byte),   V_n[c] = v_scale[j] * e4m3(v byte)
+ * (k_scale / v_scale: [Hkv] floats, NULL = 1).  The bytes are widened exactly and the products
+ * with the scales are taken in fp64, so the only inputs are the stored bits; everything else is
+ * as in rl_decode_attn_ref_f64.  q_type is the element type of q (RLREF_F32 or RLREF_BF16).
+ * Pinned in tests/test_oracle_kv8_pins.py: the decode of all 256 byte values against the
+ * format's definition (hand values and a library conversion), and equality with
+ * rl_decode_attn_ref_f64 on the dequantised values whenever those are exact in fp32.
+ */
+int rl_decode_attn_ref_kv8_f64(int q_type, const float* k_scale, const float* v_scale,
+                               int P, int G, int Hq, int Hkv, int d,
+                               int Lp_cap, int Ls_cap, double scale,
+                               const void* q,
+                               const void* k_prefix, const void* v_prefix,
+                               const int32_t* prefix_lens,
+                               const void* k_suffix, const void* v_suffix,
+                               const int32_t* suffix_lens,
+                               double* out, double* lse,
+                               const int32_t* rows, int64_t n_rows,
+                               int n_threads, int* threads_used);
+
+/* Value of one e4m3 byte (NaN for 0x7f / 0xff). */
+double rl_e4m3_to_f64_ref(uint8_t bits);
 
 /*
  * Merge of split-softmax partials (the log-sum-exp combine step): given n

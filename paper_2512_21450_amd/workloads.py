@@ -150,11 +150,47 @@ def make_inputs(w: Workload, threads: int = 8) -> dict:
     }
 
 
-def algorithmic_bytes(w: Workload, prefix_lens, suffix_lens) -> dict:
+E4M3_MAX = 448.0          # largest finite e4m3 value
+
+
+def kv_to_e4m3(x: dict, chunk_rows: int = 8) -> dict:
+    """Re-store the K/V buffers of a bf16 batch as e4m3 bytes with one scale per KV head.
+
+    Data preparation only (the quantiser a serving engine runs when it fills an 8-bit KV cache):
+    ``k_scale[j]`` = largest |k| of KV head j over prefix and suffix stores / 448, likewise
+    ``v_scale``; every element is divided by its head's scale and rounded to the nearest e4m3
+    value (ties to even) by torch's CPU conversion.  The attention operates on the stored bytes
+    and scales; what they were rounded from plays no further role.
+    """
+    import torch
+    y = dict(x)
+    for name in ("k", "v"):
+        stores = [x[f"{name}_prefix"], x[f"{name}_suffix"]]
+        Hkv = stores[0].shape[1]
+        amax = np.zeros(Hkv, np.float32)
+        for a in stores:
+            for i in range(0, a.shape[0], chunk_rows):
+                f = bf16_bits_to_f32(a[i:i + chunk_rows]) if a.dtype == np.uint16 else a[i:i + chunk_rows]
+                if f.size:
+                    amax = np.maximum(amax, np.abs(f).max(axis=(0, 2, 3)))
+        sc = np.where(amax > 0, amax / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+        for a, key in zip(stores, (f"{name}_prefix", f"{name}_suffix")):
+            out = np.empty(a.shape, np.uint8)
+            for i in range(0, a.shape[0], chunk_rows):
+                f = bf16_bits_to_f32(a[i:i + chunk_rows]) if a.dtype == np.uint16 else a[i:i + chunk_rows]
+                t = torch.from_numpy(np.ascontiguousarray(f / sc[None, :, None, None]))
+                out[i:i + chunk_rows] = t.clamp_(-E4M3_MAX, E4M3_MAX).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+            y[key] = out
+        y[f"{name}_scale"] = sc
+    return y
+
+
+def algorithmic_bytes(w: Workload, prefix_lens, suffix_lens, kv_elem_bytes: int = 0) -> dict:
     """Bytes one decode step has to move, from the realised lengths: each
     prompt's prefix K/V once, each sequence's own suffix K/V once, q in,
-    out (fp32) and lse (fp32) out, and the two length arrays."""
-    row = w.Hkv * 2 * w.d * w.elem_bytes                      # K+V bytes per token, all KV heads
+    out (fp32) and lse (fp32) out, and the two length arrays.
+    ``kv_elem_bytes``: bytes per stored K/V element when it differs from q's (1 for e4m3)."""
+    row = w.Hkv * 2 * w.d * (kv_elem_bytes or w.elem_bytes)   # K+V bytes per token, all KV heads
     prefix = int(np.sum(prefix_lens, dtype=np.int64)) * row
     suffix = int(np.sum(suffix_lens, dtype=np.int64)) * row
     io = w.B * w.Hq * w.d * w.elem_bytes + w.B * w.Hq * w.d * 4 + w.B * w.Hq * 4 + 4 * (w.P + w.B)
@@ -179,7 +215,8 @@ def to_pages(x: dict, page_size: int, seed: int, spare_pages: int = 3, poison: b
     n_pages = int(need.sum()) + spare_pages
     max_pages = max((Ls_cap + page_size - 1) // page_size, 1)
     order = np.random.default_rng(seed).permutation(n_pages)
-    nan_bits = np.uint16(0x7FC0) if ks.dtype == np.uint16 else np.float32(np.nan)
+    nan_bits = {np.dtype(np.uint16): np.uint16(0x7FC0), np.dtype(np.uint8): np.uint8(0x7F)}.get(
+        ks.dtype, np.float32(np.nan))
     fill = nan_bits if poison else ks.dtype.type(0)
     kp = np.full((n_pages, Hkv, page_size, d), fill, dtype=ks.dtype)
     vp = np.full((n_pages, Hkv, page_size, d), fill, dtype=vs.dtype)
