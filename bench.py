@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--event-every", type=int, default=8, help="record per-kernel HIP events on every n-th step")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
+    ap.add_argument("--kv", default="bf16", choices=["bf16", "e4m3"],
+                    help="element type of the K/V stores (e4m3: one byte per element plus a factor per KV head; "
+                         "q and the arithmetic stay bf16)")
     ap.add_argument("--naive-steps", type=int, default=20,
                     help="steps of the unoptimised GPU kernel timed as a reference row (0 = skip)")
     ap.add_argument("--page-size", type=int, default=0,
@@ -98,6 +101,11 @@ def main():
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
     x = wl.make_inputs(w, threads=16)
+    kv8 = args.kv == "e4m3"
+    if kv8:
+        if w.dtype != "bf16":
+            sys.exit("bench.py: --kv e4m3 needs a bf16 workload")
+        x = wl.kv_to_e4m3(x)
     paged = args.page_size > 0
     active = None
     x0 = x                                    # contiguous layout, kept for the CPU leg
@@ -110,7 +118,8 @@ def main():
     # bytes the step must move: finished sequences contribute nothing, a prompt only if one of its sequences is live
     live_b = np.ones(w.B, bool) if active is None else active.astype(bool)
     live_p = live_b.reshape(w.P, w.G).any(axis=1)
-    ab = wl.algorithmic_bytes(w, np.where(live_p, x["prefix_lens"], 0), np.where(live_b, x["suffix_lens"], 0))
+    ab = wl.algorithmic_bytes(w, np.where(live_p, x["prefix_lens"], 0), np.where(live_b, x["suffix_lens"], 0),
+                              kv_elem_bytes=1 if kv8 else 0)
 
     def dev_t(a):
         if a.dtype == np.uint16:
@@ -129,10 +138,11 @@ def main():
         if paged:
             ds = B.paged_desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_pages"],
                                            s["v_pages"], s["block_table"], s["suffix_lens"], w.scale, w.G, out, lse,
-                                           act_t, None, algo)
+                                           act_t, None, algo, s.get("k_scale"), s.get("v_scale"))
         else:
             ds = B.desc_from_tensors(s["q"], s["k_prefix"], s["v_prefix"], s["prefix_lens"], s["k_suffix"],
-                                     s["v_suffix"], s["suffix_lens"], w.scale, w.G, out, lse, None, algo)
+                                     s["v_suffix"], s["suffix_lens"], w.scale, w.G, out, lse, None, algo,
+                                     s.get("k_scale"), s.get("v_scale"))
         if ws is None:
             need = B.rl_decode_attn_paged_workspace_bytes(ds) if paged else B.rl_decode_attn_workspace_bytes(ds)
             ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
@@ -190,9 +200,10 @@ def main():
         if paged:
             return ref.decode_attn_paged_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_pages"],
                                              x["v_pages"], x["block_table"], x["suffix_lens"], active, w.scale, w.G,
-                                             **kw)
+                                             k_scale=x.get("k_scale"), v_scale=x.get("v_scale"), **kw)
         return ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_suffix"],
-                                   x["v_suffix"], x["suffix_lens"], w.scale, w.G, **kw)
+                                   x["v_suffix"], x["suffix_lens"], w.scale, w.G,
+                                   k_scale=x.get("k_scale"), v_scale=x.get("v_scale"), **kw)
 
     ro, rl = oracle(rows=rows)
     step(0)
@@ -214,7 +225,8 @@ def main():
         while True:                           # whole passes over the sample until about 10 s of wall time
             _, _, used = ref.decode_attn_ref(x0["q"], x0["k_prefix"], x0["v_prefix"], x0["prefix_lens"],
                                              x0["k_suffix"], x0["v_suffix"], x0["suffix_lens"], w.scale, w.G,
-                                             rows=rws, return_threads=True)
+                                             rows=rws, return_threads=True,
+                                             k_scale=x0.get("k_scale"), v_scale=x0.get("v_scale"))
             passes += 1
             c1 = time.perf_counter()
             if c1 - c0 >= args.cpu_seconds:
@@ -228,7 +240,8 @@ def main():
         r1 = np.stack([np.repeat(s1, w.Hq), np.tile(np.arange(w.Hq, dtype=np.int32), len(s1))], 1)
         c0 = time.perf_counter()
         ref.decode_attn_ref(x0["q"], x0["k_prefix"], x0["v_prefix"], x0["prefix_lens"], x0["k_suffix"],
-                            x0["v_suffix"], x0["suffix_lens"], w.scale, w.G, rows=r1, n_threads=1)
+                            x0["v_suffix"], x0["suffix_lens"], w.scale, w.G, rows=r1, n_threads=1,
+                            k_scale=x0.get("k_scale"), v_scale=x0.get("v_scale"))
         cpu["one_thread_value"] = len(s1) / (time.perf_counter() - c0)
         cpu["one_thread_sample"] = f"{len(s1)} sequences, one pass"
 
@@ -266,6 +279,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.note}; suffix {w.suffix}", "P": w.P, "G": w.G, "Hq": w.Hq,
                    "Hkv": w.Hkv, "d": w.d, "algo": {1: "simple", 2: "shared"}.get(plan, str(plan)),
                    "suffix_store": f"paged, {args.page_size} rows per page" if paged else "contiguous",
+                   "kv_store": "e4m3 bytes, one factor per KV head" if kv8 else w.dtype,
                    "finished_sequences": int((~live_b).sum()),
                    "kv_sets_rotated": len(sets),
                    "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
@@ -274,7 +288,7 @@ def main():
         "pct_of_hbm_peak_whole_step": 100.0 * ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes": ab,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if paged else measured_traffic(w.name, plan),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if paged or kv8 else measured_traffic(w.name, plan),
                      "kernel": "partial_kernel" if plan == 2 else "simple_kernel",
                      "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
                      "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),

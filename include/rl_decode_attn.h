@@ -44,8 +44,24 @@
 extern "C" {
 #endif
 
-/* Element type of q, k_*, v_*.  out and lse are always fp32. */
-typedef enum { RLDA_F32 = 0, RLDA_BF16 = 1 } rlda_dtype;
+/*
+ * Element types.  out and lse are always fp32.
+ *   RLDA_F32, RLDA_BF16   q and the K/V stores all hold this type.
+ *   RLDA_BF16_KV8         q is bf16; the K/V stores (prefix, suffix or pages) hold one byte per
+ *                         element, the e4m3 encoding of the OCP 8-bit floating point format (1 sign,
+ *                         4 exponent bits with bias 7, 3 mantissa bits, subnormals, no infinity,
+ *                         S.1111.111 = NaN, largest finite value 448), with one dequantisation factor
+ *                         per KV head:  K_n[c] = k_scale[j] * e4m3(byte),  V_n[c] = v_scale[j] * e4m3(byte).
+ *                         The rollout of Algorithm 1 is bound by reading the K/V of every live
+ *                         trajectory once per generated token (Sec. 3.2.2 "Sampling stage"); a one-byte
+ *                         store halves those bytes.  The call computes the attention of the header
+ *                         comment on exactly these dequantised values (every e4m3 value is exact in
+ *                         bf16, so nothing is rounded on the way in); how the bytes were produced is
+ *                         the caller's business.  Both kernel families take it (d = 64 or 128; the
+ *                         usual limits of RLDA_ALGO_SHARED decide which one AUTO picks).  NaN bytes
+ *                         may sit in rows at or beyond a length like any other garbage.
+ */
+typedef enum { RLDA_F32 = 0, RLDA_BF16 = 1, RLDA_BF16_KV8 = 2 } rlda_dtype;
 
 /* Kernel selection. */
 typedef enum {
@@ -89,6 +105,8 @@ typedef struct {
   float*   lse;                /* [B, Hq]    fp32, natural log; may be NULL                      */
   void*    workspace;          /* device scratch, 256-byte aligned, may be NULL if 0 bytes needed */
   size_t   workspace_bytes;
+  const float* k_scale;        /* [Hkv] fp32, RLDA_BF16_KV8 only (else ignored); NULL = all 1     */
+  const float* v_scale;        /* [Hkv] fp32, likewise                                           */
 } rlda_desc;
 
 /*
@@ -195,6 +213,8 @@ typedef struct {
   float*   lse;                /* [B, Hq] fp32; may be NULL                                      */
   void*    workspace;
   size_t   workspace_bytes;    /* >= rl_decode_attn_paged_workspace_bytes                        */
+  const float* k_scale;        /* [Hkv] fp32, RLDA_BF16_KV8 only; NULL = all 1                   */
+  const float* v_scale;        /* [Hkv] fp32, likewise                                           */
 } rlda_paged_desc;
 
 int    rl_decode_attn_paged(const rlda_paged_desc* desc, void* hip_stream, void* mid_event);

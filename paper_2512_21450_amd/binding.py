@@ -26,7 +26,7 @@ if not os.path.exists(LIB_PATH):
 
 _lib = ctypes.CDLL(LIB_PATH)
 
-RLDA_F32, RLDA_BF16 = 0, 1
+RLDA_F32, RLDA_BF16, RLDA_BF16_KV8 = 0, 1, 2
 RLDA_ALGO_AUTO, RLDA_ALGO_SIMPLE, RLDA_ALGO_SHARED = 0, 1, 2
 RLDA_OK, RLDA_ERR_INVALID, RLDA_ERR_UNSUPPORTED = 0, -1, -2
 RLDA_ERR_WORKSPACE, RLDA_ERR_STRUCT_SIZE, RLDA_ERR_LAUNCH = -3, -4, -5
@@ -46,6 +46,7 @@ class rlda_desc(ctypes.Structure):
         ("k_suffix", ctypes.c_void_p), ("v_suffix", ctypes.c_void_p), ("suffix_lens", ctypes.c_void_p),
         ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -65,6 +66,7 @@ class rlda_paged_desc(ctypes.Structure):
         ("suffix_lens", ctypes.c_void_p), ("seq_active", ctypes.c_void_p),
         ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+        ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -153,8 +155,27 @@ def _torch_dtype_code(t):
     raise TypeError(f"q/k/v must be float32 or bfloat16, got {t.dtype}")
 
 
+def _kv_dtype_code(q, stores, k_scale, v_scale):
+    """Descriptor dtype for q and its K/V stores; e4m3 stores are uint8 (or torch.float8_e4m3fn) tensors."""
+    import torch
+    code = _torch_dtype_code(q)
+    kv8 = [t.dtype in (torch.uint8, torch.float8_e4m3fn) for t in stores]
+    if all(kv8):
+        if code != RLDA_BF16:
+            raise TypeError("e4m3 K/V stores go with a bfloat16 q")
+        for sc in (k_scale, v_scale):
+            if sc is not None and (sc.dtype != torch.float32 or sc.numel() != stores[0].shape[1] or not sc.is_contiguous()):
+                raise TypeError("k_scale / v_scale must be contiguous float32 [Hkv]")
+        return RLDA_BF16_KV8
+    if any(kv8) or any(_torch_dtype_code(t) != code for t in stores):
+        raise TypeError("q/k/v dtypes differ")
+    if k_scale is not None or v_scale is not None:
+        raise TypeError("k_scale / v_scale belong to e4m3 K/V stores")
+    return code
+
+
 def desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
-                      out, lse=None, workspace=None, algo=RLDA_ALGO_AUTO) -> rlda_desc:
+                      out, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, k_scale=None, v_scale=None) -> rlda_desc:
     """Descriptor over torch device tensors (shapes as in the header)."""
     B, Hq, d = q.shape
     P, Hkv, Lp_cap, _ = k_prefix.shape
@@ -164,20 +185,18 @@ def desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, su
     for t in (q, k_prefix, v_prefix, k_suffix, v_suffix, prefix_lens, suffix_lens, out):
         if not t.is_contiguous():
             raise ValueError("tensors must be contiguous")
-    code = _torch_dtype_code(q)
-    for t in (k_prefix, v_prefix, k_suffix, v_suffix):
-        if _torch_dtype_code(t) != code:
-            raise TypeError("q/k/v dtypes differ")
+    code = _kv_dtype_code(q, (k_prefix, v_prefix, k_suffix, v_suffix), k_scale, v_scale)
     ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
     return make_desc(code, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale), algo,
                      q=ptr(q), k_prefix=ptr(k_prefix), v_prefix=ptr(v_prefix), prefix_lens=ptr(prefix_lens),
                      k_suffix=ptr(k_suffix), v_suffix=ptr(v_suffix), suffix_lens=ptr(suffix_lens),
                      out=ptr(out), lse=ptr(lse), workspace=ptr(workspace),
-                     workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+                     workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size(),
+                     k_scale=ptr(k_scale), v_scale=ptr(v_scale))
 
 
 def rl_decode_attn(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
-                   out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None):
+                   out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None, k_scale=None, v_scale=None):
     """One decode-attention step on torch device tensors; returns (out, lse).
 
     Allocates out/lse/workspace with torch when they are not passed in.  The
@@ -192,7 +211,7 @@ def rl_decode_attn(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffi
     if lse is None:
         lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
     ds = desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
-                           out, lse, workspace, algo)
+                           out, lse, workspace, algo, k_scale, v_scale)
     if workspace is None:
         need = rl_decode_attn_workspace_bytes(ds)
         if need:
@@ -234,7 +253,7 @@ def rl_decode_attn_paged_raw(desc: rlda_paged_desc, stream_handle=None, mid_even
 
 def paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
                             scale, G, out, lse=None, seq_active=None, workspace=None,
-                            algo=RLDA_ALGO_AUTO) -> rlda_paged_desc:
+                            algo=RLDA_ALGO_AUTO, k_scale=None, v_scale=None) -> rlda_paged_desc:
     """Paged descriptor over torch device tensors (shapes as in the header)."""
     import torch
     B, Hq, d = q.shape
@@ -247,21 +266,20 @@ def paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages
     for t in (q, k_prefix, v_prefix, k_pages, v_pages, prefix_lens, suffix_lens, block_table, out):
         if not t.is_contiguous():
             raise ValueError("tensors must be contiguous")
-    code = _torch_dtype_code(q)
-    for t in (k_prefix, v_prefix, k_pages, v_pages):
-        if _torch_dtype_code(t) != code:
-            raise TypeError("q/k/v dtypes differ")
+    code = _kv_dtype_code(q, (k_prefix, v_prefix, k_pages, v_pages), k_scale, v_scale)
     ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
     return make_paged_desc(code, P, G, Hq, Hkv, d, Lp_cap, page_size, block_table.shape[1], n_pages, float(scale),
                            algo, q=ptr(q), k_prefix=ptr(k_prefix), v_prefix=ptr(v_prefix),
                            prefix_lens=ptr(prefix_lens), k_pages=ptr(k_pages), v_pages=ptr(v_pages),
                            block_table=ptr(block_table), suffix_lens=ptr(suffix_lens), seq_active=ptr(seq_active),
                            out=ptr(out), lse=ptr(lse), workspace=ptr(workspace),
-                           workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+                           workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size(),
+                           k_scale=ptr(k_scale), v_scale=ptr(v_scale))
 
 
 def rl_decode_attn_paged(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens, scale, G,
-                         seq_active=None, out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None):
+                         seq_active=None, out=None, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, stream=None,
+                         k_scale=None, v_scale=None):
     """One decode step over a paged suffix store; returns (out, lse).  Asynchronous on ``stream``."""
     import torch
     if not q.is_cuda:
@@ -272,7 +290,7 @@ def rl_decode_attn_paged(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, b
     if lse is None:
         lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
     ds = paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, block_table, suffix_lens,
-                                 scale, G, out, lse, seq_active, workspace, algo)
+                                 scale, G, out, lse, seq_active, workspace, algo, k_scale, v_scale)
     if workspace is None:
         need = rl_decode_attn_paged_workspace_bytes(ds)
         if need:

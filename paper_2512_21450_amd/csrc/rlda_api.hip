@@ -21,6 +21,7 @@ int to_problem(const rlda_desc* ds, Problem& pb) {
   pb.q = ds->q; pb.k_prefix = ds->k_prefix; pb.v_prefix = ds->v_prefix; pb.prefix_lens = ds->prefix_lens;
   pb.k_suffix = ds->k_suffix; pb.v_suffix = ds->v_suffix; pb.suffix_lens = ds->suffix_lens;
   pb.out = ds->out; pb.lse = ds->lse; pb.workspace = ds->workspace; pb.workspace_bytes = ds->workspace_bytes;
+  if (ds->dtype == RLDA_BF16_KV8) { pb.k_scale = ds->k_scale; pb.v_scale = ds->v_scale; }
   return RLDA_OK;
 }
 
@@ -42,13 +43,14 @@ int to_problem(const rlda_paged_desc* ds, Problem& pb) {
   pb.max_pages = ds->max_pages; pb.n_pages = ds->n_pages;
   pb.seq_active = ds->seq_active;
   pb.out = ds->out; pb.lse = ds->lse; pb.workspace = ds->workspace; pb.workspace_bytes = ds->workspace_bytes;
+  if (ds->dtype == RLDA_BF16_KV8) { pb.k_scale = ds->k_scale; pb.v_scale = ds->v_scale; }
   return RLDA_OK;
 }
 
 int check_shape(const Problem& pb) {
   if (pb.P < 0 || pb.G < 0 || pb.Hq <= 0 || pb.Hkv <= 0 || pb.d <= 0 || pb.Lp_cap < 0 || pb.Ls_cap < 0)
     return RLDA_ERR_INVALID;
-  if (pb.dtype != RLDA_F32 && pb.dtype != RLDA_BF16) return RLDA_ERR_UNSUPPORTED;
+  if (pb.dtype != RLDA_F32 && pb.dtype != RLDA_BF16 && pb.dtype != RLDA_BF16_KV8) return RLDA_ERR_UNSUPPORTED;
   if (pb.algo != RLDA_ALGO_AUTO && pb.algo != RLDA_ALGO_SIMPLE && pb.algo != RLDA_ALGO_SHARED)
     return RLDA_ERR_UNSUPPORTED;
   if (pb.d != 64 && pb.d != 128) return RLDA_ERR_UNSUPPORTED;
@@ -119,7 +121,7 @@ extern "C" {
 
 const char* rl_decode_attn_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
-int rl_decode_attn_version(void) { return 200; }
+int rl_decode_attn_version(void) { return 300; }
 
 const char* rl_decode_attn_strerror(int code) {
   switch (code) {

@@ -27,12 +27,16 @@ struct Problem {
   const uint8_t* seq_active;      // null: every sequence is live
   float* out; float* lse;
   void* workspace; size_t workspace_bytes;
+  const float* k_scale; const float* v_scale;   // per-KV-head factors of an e4m3 K/V store, or null
 };
 
-// ---- simple path: one wavefront per (sequence, query head); fp32 or bf16; d in {64,128}
+// bytes per stored K/V element
+inline int kv_elem_bytes(int dtype) { return dtype == RLDA_F32 ? 4 : (dtype == RLDA_BF16_KV8 ? 1 : 2); }
+
+// ---- simple path: one wavefront per (sequence, query head); fp32, bf16 or bf16 with e4m3 K/V; d in {64,128}
 hipError_t launch_simple(const Problem& pb, hipStream_t stream);
 
-// ---- shared-prefix MFMA path (bf16, d = 128)
+// ---- shared-prefix MFMA path (bf16 or bf16 with e4m3 K/V, d = 128)
 bool   shared_supported(const Problem& pb);
 size_t shared_workspace_bytes(const Problem& pb);
 // `mid`, if not null, is recorded between the partial kernel and the combine kernel

@@ -1,4 +1,5 @@
 // Shared-prefix decode attention on gfx950 matrix cores (bf16 in, fp32 accumulate, d = 128).
+// K/V stores hold bf16, or e4m3 bytes that are widened to bf16 (exactly) on their way into LDS.
 //
 // Two kernels per call:
 //   partial_kernel  walks the static tile partition of rlda_sched.h with two workgroups of four
@@ -30,7 +31,7 @@ namespace rlda {
 namespace {
 
 constexpr int D = 128;
-constexpr int ROWB = D * 2;                       // bytes per K/V row
+constexpr int ROWB = D * 2;                       // bytes per K/V row in LDS (and in a bf16 store; also a q row)
 constexpr int TILE_B = TK * ROWB;                 // 8 KB: one K or V tile
 constexpr int STAGE_B = 2 * TILE_B;               // K tile + V tile
 constexpr int NTHREADS = 64 * WG_WAVES;
@@ -65,6 +66,8 @@ struct SharedParams {
   const int32_t* table;   // [B, max_pages] page ids when ks / vs are page pools [n_pages, Hkv, page, D], else null
   const uint8_t* active;  // [B] finished-sequence flags, or null
   int page_shift, max_pages, n_pages;
+  // e4m3 K/V stores only (kernels instantiated with F8 = true): per-KV-head factors, or null
+  const float* kscale; const float* vscale;
 };
 
 // Effective lengths: clamped to the capacity; in the extended form a finished sequence has no
@@ -223,7 +226,7 @@ __device__ __forceinline__ int part_col_off(int q) {
 // tolerance of the bf16 path, whose weights are already rounded to bf16.
 template <int NT>
 __device__ __forceinline__ void write_partial(const WaveState<NT>& st, _Float16* po, float* pl, int slot, int nrows,
-                                              int rowbase, int lane) {
+                                              int rowbase, int lane, float vfac) {
   const int m16 = lane & 15, g = lane >> 4;
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
@@ -238,7 +241,7 @@ __device__ __forceinline__ void write_partial(const WaveState<NT>& st, _Float16*
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64)); mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
     const int row = rowbase + 16 * nt + m16;
     if (row < nrows) {
-      const float inv = 1.f / lr;
+      const float inv = vfac / lr;                           // vfac: factor of the V store (1 unless e4m3)
       const int e = clampi((int)((__float_as_uint(mx * inv) >> 23) & 255u), 1, 252);   // max |o| in [2^(e-127), 2^(e-126))
       const float k = inv * __uint_as_float((uint32_t)(253 - e) << 23);                // o * 2^(126-e) in [0.5, 1)
       char* o = reinterpret_cast<char*>(po + ((size_t)slot * nrows + row) * D);
@@ -261,6 +264,57 @@ __device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast
 // K/V rows are read exactly once per call: stream them past the caches
 __device__ __forceinline__ u32x4 ldg16_stream(const char* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+// ---- how a wavefront moves one 32-key K (or V) tile from the store to LDS.
+// bf16 store: 8 instructions of 16 bytes per lane, instruction i covering tile rows 4i .. 4i+3
+// (16 lanes per 256-byte row).  e4m3 store: 4 instructions, instruction i covering rows 8i .. 8i+7
+// (8 lanes per 128-byte row); a lane's 16 bytes become two adjacent 16-byte bf16 chunks in LDS.
+template <bool F8>
+struct Stage {
+  static constexpr int NL = F8 ? 4 : 8;                     // load instructions per tile
+  static constexpr int GROWB = F8 ? D : 2 * D;              // bytes per row in the store
+  static constexpr int RS = F8 ? 8 : 4;                     // tile rows per instruction
+  // instruction i of lane `lane` fetches 16 bytes: chunk chunk(lane) of tile row RS * i + lrow(lane)
+  __device__ static __forceinline__ int lrow(int lane) { return F8 ? lane >> 3 : lane >> 4; }
+  __device__ static __forceinline__ int chunk(int lane) { return F8 ? lane & 7 : lane & 15; }
+};
+
+// four e4m3 bytes -> four bf16 (exact: 4 significant bits, exponents inside bf16's range), with
+// gfx950's packed converter: two bytes of the source word per instruction, scaled by 2^0
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ u32x2 e4m3x4_to_bf16(uint32_t w) {
+  const bf16x2 lo = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);   // bytes 0, 1
+  const bf16x2 hi = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);    // bytes 2, 3
+  return u32x2{*reinterpret_cast<const uint32_t*>(&lo), *reinterpret_cast<const uint32_t*>(&hi)};
+}
+// 16 e4m3 bytes -> two 16-byte chunks of 8 bf16
+__device__ __forceinline__ void e4m3x16_to_bf16(const u32x4& w, u32x4& lo, u32x4& hi) {
+  const u32x2 a = e4m3x4_to_bf16(w[0]), b = e4m3x4_to_bf16(w[1]), c = e4m3x4_to_bf16(w[2]), d = e4m3x4_to_bf16(w[3]);
+  lo = u32x4{a[0], a[1], b[0], b[1]};
+  hi = u32x4{c[0], c[1], d[0], d[1]};
+}
+
+// registers of one tile -> LDS (K tile at Kl, V tile at Vl), in the swizzled layout compute_tile reads
+template <bool F8>
+__device__ __forceinline__ void stage_store(char* Kl, char* Vl, const u32x4 (&rk)[Stage<F8>::NL],
+                                            const u32x4 (&rv)[Stage<F8>::NL], int lrow, int chunk) {
+#pragma unroll
+  for (int i = 0; i < Stage<F8>::NL; ++i) {
+    const int row = Stage<F8>::RS * i + lrow;
+    if (!F8) {
+      lds_st128(Kl + k_off(row, chunk), rk[i]);
+      lds_st128(Vl + v_off(row, chunk), rv[i]);
+    } else {
+      u32x4 a, b;
+      e4m3x16_to_bf16(rk[i], a, b);
+      lds_st128(Kl + k_off(row, 2 * chunk), a);
+      lds_st128(Kl + k_off(row, 2 * chunk + 1), b);
+      e4m3x16_to_bf16(rv[i], a, b);
+      lds_st128(Vl + v_off(row, 2 * chunk), a);
+      lds_st128(Vl + v_off(row, 2 * chunk + 1), b);
+    }
+  }
 }
 
 // locate() of the partition, evaluated by a whole wavefront at once (all lanes active, same
@@ -313,22 +367,25 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, in
 // memory pipeline and the matrix pipeline of the CU overlap and no bubble opens at a unit
 // boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
 // merged through LDS and the partial is written.
-template <int NRB, int NT, bool EXT>
+template <int NRB, int NT, bool EXT, bool F8>
 __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int tid) {
   auto len_of = [&](int p) { return plen_of<EXT>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  constexpr int LPS = 8 / NRB;                              // loads (of K and of V) per slice
+  using St = Stage<F8>;
+  constexpr int NL = St::NL, GROWB = St::GROWB;
+  constexpr int LPS = NL / NRB;                             // loads (of K and of V) per slice
   const int rb = wv & (NRB - 1), part = wv / NRB, s_lo = part * NRB;
   const int rowbase = 16 * NT * rb;                         // inside the unit's row half
-  const int lrow = lane >> 4, chunk = lane & 15;
+  const int lrow = St::lrow(lane), chunk = St::chunk(lane);
   auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
   auto head_of = [&](const Cur& c) { return c.j >> P.NHs; };
   char* mine = lds + wv * STAGE_B;
 
   constexpr bool QPRE = NT == 1;                            // query rows of the next unit are prefetched (one block per wavefront)
-  u32x4 rk[8], rv[8], qn[QPRE ? NT : 1][4];
+  u32x4 rk[NL], rv[NL], qn[QPRE ? NT : 1][4];
   bf16x8 qf[NT][4];
   WaveState<NT> st;
+  float cu = P.c;                                           // score factor of the current unit
   auto issue_q = [&](const Cur& c) {                        // row = sample * r + head-in-group
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
@@ -348,12 +405,12 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   int rem = n, gs = group_size(cur, rem);
   if (QPRE) issue_q(cur);
   if (wv < gs) {
-    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * ROWB;
-    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * ROWB;
+    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * GROWB;
+    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * GROWB;
     const int key0 = (cur.t + wv) * TK, last = min(TK, cur.L - key0) - 1;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+    for (int i = 0; i < NL; ++i) {
+      const size_t off = (size_t)(key0 + min(St::RS * i + lrow, last)) * GROWB + 16 * chunk;
       rk[i] = ldg16_stream(kb + off);
       rv[i] = ldg16_stream(vb + off);
     }
@@ -362,14 +419,9 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   while (rem > 0) {
     const bool active = 64 * half_of(cur) + rowbase < P.R;  // this wavefront's row block exists in the unit's half
     wait_vmem();
-    if (wv < gs) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        lds_st128(mine + k_off(4 * i + lrow, chunk), rk[i]);
-        lds_st128(mine + TILE_B + v_off(4 * i + lrow, chunk), rv[i]);
-      }
-    }
+    if (wv < gs) stage_store<F8>(mine, mine + TILE_B, rk, rv, lrow, chunk);
     if (fresh) {
+      if (F8 && P.kscale) cu = P.c * P.kscale[head_of(cur)];
       if (QPRE) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
@@ -393,17 +445,17 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
     lds_barrier();
     if (QPRE && next_fresh) issue_q(nxt);
     const bool more = wv < ngs;                             // this wavefront fetches a tile of the next group
-    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * ROWB;
-    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * ROWB;
+    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * GROWB;
+    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * GROWB;
     const int key0 = (nxt.t + wv) * TK, last = min(TK, nxt.L - key0) - 1;
     // the upper half of the wavefronts issues a slice before each tile computation, the lower half
     // after it, so that they alternate between the memory pipeline and the matrix pipeline
     const bool first = wv >= WG_WAVES / 2;
     auto slice = [&](int k) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {                         // rows past the length re-read the last real row
+      for (int i = 0; i < NL; ++i) {                        // rows past the length re-read the last real row
         if (i >= k * LPS && i < (k + 1) * LPS) {
-          const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+          const size_t off = (size_t)(key0 + min(St::RS * i + lrow, last)) * GROWB + 16 * chunk;
           rk[i] = ldg16_stream(kb + off);
           rv[i] = ldg16_stream(vb + off);
         }
@@ -415,7 +467,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       if (more && first) slice(k);
       if (active && s < gs)
         compute_tile<NT>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, cur.L - (cur.t + s) * TK), qf, st,
-                        P.c, lane);
+                        F8 ? cu : P.c, lane);
       if (more && !first) slice(k);
     }
     lds_barrier();                                          // stages are rewritten by the next group
@@ -460,7 +512,9 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
         }
         lds_barrier();                                      // parked state is dead before tiles are stored again
       }
-      if (active && part == 0) write_partial<NT>(st, P.po, P.pl, cur.u * P.HkvP + cur.j + rank, P.RS, rowbase, lane);
+      if (active && part == 0)
+        write_partial<NT>(st, P.po, P.pl, cur.u * P.HkvP + cur.j + rank, P.RS, rowbase, lane,
+                          F8 && P.vscale ? P.vscale[head_of(cur)] : 1.f);
     }
     fresh = next_fresh; cur = nxt; rem = rem2; gs = ngs;
   }
@@ -469,32 +523,35 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
 // ---- suffix tiles of one wavefront: `n` tiles of the line starting at `cur`, streamed through the
 // wavefront's private 16 KB of LDS.  The loads of tile i + 1 (and the query rows of its unit when
 // it starts a new one) are in flight while tile i is computed, across unit boundaries as well.
-template <bool EXT>
+template <bool EXT, bool F8>
 __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds, Cur cur, int n, int slot_base,
                                               int lane) {
   auto len_of = [&](int b) { return slen_of<EXT>(P, b); };
-  const int m16 = lane & 15, g = lane >> 4, lrow = lane >> 4, chunk = lane & 15;
-  u32x4 rk[8], rv[8], qn[4];
+  using St = Stage<F8>;
+  constexpr int NL = St::NL, GROWB = St::GROWB;
+  const int m16 = lane & 15, g = lane >> 4, lrow = St::lrow(lane), chunk = St::chunk(lane);
+  u32x4 rk[NL], rv[NL], qn[4];
   bf16x8 qf[1][4];
   WaveState<1> st;
+  float cu = P.c;                                           // score factor of the current unit
   auto issue_q = [&](const Cur& c) {
     const bool ok = m16 < P.r;
     const char* qp = P.q + ((size_t)c.u * P.Hq + c.j * P.r + (ok ? m16 : 0)) * ROWB + 16 * g;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qn[ks] = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
   };
-  auto issue_tile = [&](const Cur& c) {                     // instruction i stages rows 4i + lrow: 1 KB contiguous
+  auto issue_tile = [&](const Cur& c) {                     // every instruction fetches 1 KB of contiguous rows
     const int key0 = c.t * TK, last = min(TK, c.L - key0) - 1;
     size_t row0 = (size_t)(c.u * P.Hkv + c.j) * P.Ls_cap + key0;      // first row of the tile in the store
     if (EXT && P.table) {                                   // a tile never straddles pages: TK divides the page size
       const int pg = uni(clampi(P.table[(size_t)c.u * P.max_pages + (key0 >> P.page_shift)], 0, P.n_pages - 1));
       row0 = (((size_t)pg * P.Hkv + c.j) << P.page_shift) + (key0 & ((1 << P.page_shift) - 1));
     }
-    const char* kb = P.ks + row0 * ROWB;
-    const char* vb = P.vs + row0 * ROWB;
+    const char* kb = P.ks + row0 * GROWB;
+    const char* vb = P.vs + row0 * GROWB;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {                           // rows past the length re-read the last real row
-      const size_t off = (size_t)min(4 * i + lrow, last) * ROWB + 16 * chunk;
+    for (int i = 0; i < NL; ++i) {                          // rows past the length re-read the last real row
+      const size_t off = (size_t)min(St::RS * i + lrow, last) * GROWB + 16 * chunk;
       rk[i] = ldg16_stream(kb + off);
       rv[i] = ldg16_stream(vb + off);
     }
@@ -504,12 +561,9 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   bool fresh = true;
   for (int i = 0; i < n; ++i) {
     wait_vmem();
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      lds_st128(wlds + k_off(4 * k + lrow, chunk), rk[k]);
-      lds_st128(wlds + TILE_B + v_off(4 * k + lrow, chunk), rv[k]);
-    }
+    stage_store<F8>(wlds, wlds + TILE_B, rk, rv, lrow, chunk);
     if (fresh) {
+      if (F8 && P.kscale) cu = P.c * P.kscale[cur.j];
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) qf[0][ks] = *reinterpret_cast<bf16x8*>(&qn[ks]);
       init_state(st);
@@ -525,15 +579,17 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    compute_tile<1>(wlds, wlds + TILE_B, min(TK, cur.L - cur.t * TK), qf, st, P.c, lane);
+    compute_tile<1>(wlds, wlds + TILE_B, min(TK, cur.L - cur.t * TK), qf, st, F8 ? cu : P.c, lane);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    if (!has_next || next_fresh) write_partial<1>(st, P.so, P.sl, cur.u * P.Hkv + cur.j + slot_base, P.r, 0, lane);
+    if (!has_next || next_fresh)
+      write_partial<1>(st, P.so, P.sl, cur.u * P.Hkv + cur.j + slot_base, P.r, 0, lane,
+                       F8 && P.vscale ? P.vscale[cur.j] : 1.f);
     fresh = next_fresh; cur = nxt;
   }
 }
 
-template <int NRB, int NT, bool EXT>
+template <int NRB, int NT, bool EXT, bool F8>
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -589,12 +645,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
     cur_load(c, [&](int p) { return plen_of<EXT>(P, p); });
-    prefix_stream<NRB, NT, EXT>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
+    prefix_stream<NRB, NT, EXT, F8>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
     cur_load(c, [&](int b) { return slen_of<EXT>(P, b); });
-    suffix_stream<EXT>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane);
+    suffix_stream<EXT, F8>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane);
   }
 }
 
@@ -710,7 +766,7 @@ Layout layout(const Problem& ds) {
 }  // namespace
 
 bool shared_supported(const Problem& ds) {
-  if (ds.dtype != RLDA_BF16 || ds.d != D) return false;
+  if ((ds.dtype != RLDA_BF16 && ds.dtype != RLDA_BF16_KV8) || ds.d != D) return false;
   const int64_t B = (int64_t)ds.P * ds.G;
   const int r = ds.Hq / ds.Hkv;
   if (r > 16 || (int64_t)r * ds.G > MAX_GROUP_ROWS) return false;       // rows of one KV group: <= 4 parts of 64
@@ -749,11 +805,15 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   P.table = ds.block_table; P.active = ds.seq_active;
   P.page_shift = ds.page_shift; P.max_pages = ds.max_pages; P.n_pages = ds.n_pages;
   const bool ext = ds.block_table != nullptr || ds.seq_active != nullptr;
+  const bool f8 = ds.dtype == RLDA_BF16_KV8;
+  P.kscale = f8 ? ds.k_scale : nullptr; P.vscale = f8 ? ds.v_scale : nullptr;
   typedef void (*kern_t)(const SharedParams);
-  static const kern_t kerns[2][3] = {
-      {partial_kernel<1, 1, false>, partial_kernel<2, 1, false>, partial_kernel<4, 1, false>},
-      {partial_kernel<1, 1, true>, partial_kernel<2, 1, true>, partial_kernel<4, 1, true>}};
-  const kern_t kern = kerns[ext][nrb == 1 ? 0 : nrb == 2 ? 1 : 2];
+  static const kern_t kerns[12] = {       // [e4m3 store][extended form][row blocks 1, 2, 4]
+      partial_kernel<1, 1, false, false>, partial_kernel<2, 1, false, false>, partial_kernel<4, 1, false, false>,
+      partial_kernel<1, 1, true, false>,  partial_kernel<2, 1, true, false>,  partial_kernel<4, 1, true, false>,
+      partial_kernel<1, 1, false, true>,  partial_kernel<2, 1, false, true>,  partial_kernel<4, 1, false, true>,
+      partial_kernel<1, 1, true, true>,   partial_kernel<2, 1, true, true>,   partial_kernel<4, 1, true, true>};
+  const kern_t kern = kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
   // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
   {
     static std::mutex mu;
@@ -763,8 +823,8 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (int i = 0; i < 6; ++i) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i / 3][i % 3]),
+      for (int i = 0; i < 12; ++i) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }

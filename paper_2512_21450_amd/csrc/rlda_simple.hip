@@ -1,6 +1,8 @@
 // Simple decode-attention kernel: one 64-lane wavefront per (sequence, query
 // head).  No prefix sharing, no key split, plain vector ALU.  It is the fp32
-// path and the unoptimised GPU reference row of the benchmark.
+// path and the unoptimised GPU reference row of the benchmark.  K/V stores may
+// also hold e4m3 bytes (decoded here with integer operations, not with the
+// hardware converter the matrix-core path uses).
 //
 // For its (b, h) the wavefront walks the prompt prefix of prompt p = b / G and
 // then the sequence's own suffix (Sec. 3.1 of the paper: the state is the
@@ -21,6 +23,7 @@ struct SimpleParams {
   const int32_t* table;       // paged suffix store: [B, max_pages] page ids, else null
   int page_shift, max_pages, n_pages;
   const uint8_t* active;      // finished-sequence flags or null
+  const float* kscale; const float* vscale;   // per-KV-head factors of an e4m3 store, or null
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
@@ -48,6 +51,26 @@ template <> struct Vec<uint16_t> {
   __device__ static float one(const uint16_t* p) { return bf16_to_f32(*p); }
 };
 
+// e4m3: 1 sign, 4 exponent bits (bias 7), 3 mantissa bits; exponent 0 is subnormal, S.1111.111 is NaN
+__device__ __forceinline__ float e4m3_to_f32(uint32_t b) {
+  const uint32_t em = b & 0x7Fu, sign = (b & 0x80u) << 24;
+  float v;
+  if (em == 0x7Fu) v = __uint_as_float(0x7FC00000u);
+  else if (em < 8u) v = (float)em * 0.001953125f;                       // m * 2^-9
+  else v = __uint_as_float((em << 20) + (120u << 23));                  // exponent e - 7 + 127
+  return __uint_as_float(__float_as_uint(v) | sign);
+}
+template <> struct Vec<uint8_t> {
+  static constexpr int N = 16;
+  __device__ static void load(const uint8_t* p, float (&f)[16]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) f[i] = e4m3_to_f32((w[i >> 2] >> (8 * (i & 3))) & 0xFFu);
+  }
+  __device__ static float one(const uint8_t* p) { return e4m3_to_f32(*p); }
+};
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -59,7 +82,8 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <typename T, int D>
+// TQ: element type of q; T: element type of the K/V stores
+template <typename TQ, typename T, int D>
 __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
   constexpr int VN = Vec<T>::N;
   constexpr int NC = D / 64;                 // output columns per lane
@@ -75,8 +99,9 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
   const int Lp = live ? min(max(P.plens[p], 0), P.Lp_cap) : 0;
   const int Ls = live ? min(max(P.slens[b], 0), P.Ls_cap) : 0;
 
-  const T* q = static_cast<const T*>(P.q) + ((size_t)b * P.Hq + h) * D;
-  for (int c = lane; c < D; c += 64) q_sh[c] = Vec<T>::one(q + c);
+  const TQ* q = static_cast<const TQ*>(P.q) + ((size_t)b * P.Hq + h) * D;
+  for (int c = lane; c < D; c += 64) q_sh[c] = Vec<TQ>::one(q + c);
+  const float kfac = P.scale * (P.kscale ? P.kscale[j] : 1.f), vfac = P.vscale ? P.vscale[j] : 1.f;
   __syncthreads();
 
   float m = -INFINITY, l = 0.f, acc[NC];
@@ -113,7 +138,7 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
 #pragma unroll
           for (int x = 0; x < VN; ++x) dot = fmaf(q_sh[c + x], kf[x], dot);
         }
-        s = dot * P.scale;
+        s = dot * kfac;
       }
       const float m_new = fmaxf(m, wave_max(s));          // finite: the tile has >= 1 key
       const float alpha = expf(m - m_new);               // m = -inf -> 0
@@ -134,7 +159,7 @@ __global__ void __launch_bounds__(64) simple_kernel(SimpleParams P) {
     }
   }
   float* o = P.out + ((size_t)b * P.Hq + h) * D;
-  const float inv = l > 0.f ? 1.f / l : 0.f;
+  const float inv = l > 0.f ? vfac / l : 0.f;
 #pragma unroll
   for (int i = 0; i < NC; ++i) o[lane + 64 * i] = acc[i] * inv;
   if (P.lse && lane == 0) P.lse[(size_t)b * P.Hq + h] = l > 0.f ? m + logf(l) : -INFINITY;
@@ -175,16 +200,19 @@ __global__ void __launch_bounds__(256) combine_kernel(const float* __restrict__ 
 hipError_t launch_simple(const Problem& ds, hipStream_t stream) {
   SimpleParams P{ds.q, ds.k_prefix, ds.v_prefix, ds.k_suffix, ds.v_suffix, ds.prefix_lens, ds.suffix_lens,
                  ds.out, ds.lse, ds.G, ds.Hq, ds.Hkv, ds.Lp_cap, ds.Ls_cap, ds.scale,
-                 ds.block_table, ds.page_shift, ds.max_pages, ds.n_pages, ds.seq_active};
+                 ds.block_table, ds.page_shift, ds.max_pages, ds.n_pages, ds.seq_active, ds.k_scale, ds.v_scale};
   const int64_t blocks = (int64_t)ds.P * ds.G * ds.Hq;
   if (blocks == 0) return hipSuccess;
   const dim3 grid((unsigned)blocks), block(64);
   if (ds.dtype == RLDA_F32) {
-    if (ds.d == 64) hipLaunchKernelGGL((simple_kernel<float, 64>), grid, block, 0, stream, P);
-    else            hipLaunchKernelGGL((simple_kernel<float, 128>), grid, block, 0, stream, P);
+    if (ds.d == 64) hipLaunchKernelGGL((simple_kernel<float, float, 64>), grid, block, 0, stream, P);
+    else            hipLaunchKernelGGL((simple_kernel<float, float, 128>), grid, block, 0, stream, P);
+  } else if (ds.dtype == RLDA_BF16_KV8) {
+    if (ds.d == 64) hipLaunchKernelGGL((simple_kernel<uint16_t, uint8_t, 64>), grid, block, 0, stream, P);
+    else            hipLaunchKernelGGL((simple_kernel<uint16_t, uint8_t, 128>), grid, block, 0, stream, P);
   } else {
-    if (ds.d == 64) hipLaunchKernelGGL((simple_kernel<uint16_t, 64>), grid, block, 0, stream, P);
-    else            hipLaunchKernelGGL((simple_kernel<uint16_t, 128>), grid, block, 0, stream, P);
+    if (ds.d == 64) hipLaunchKernelGGL((simple_kernel<uint16_t, uint16_t, 64>), grid, block, 0, stream, P);
+    else            hipLaunchKernelGGL((simple_kernel<uint16_t, uint16_t, 128>), grid, block, 0, stream, P);
   }
   return hipGetLastError();
 }

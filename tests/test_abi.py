@@ -47,9 +47,21 @@ def good(**kw):
 
 
 def test_descriptor_layout_matches_the_header():
-    # 11 four-byte fields, padding to 8, 9 pointers, pointer + size_t
-    assert ctypes.sizeof(B.rlda_desc) == 48 + 9 * 8 + 16
+    # 11 four-byte fields, padding to 8, 9 pointers, pointer + size_t, the two scale pointers
+    assert ctypes.sizeof(B.rlda_desc) == 48 + 9 * 8 + 16 + 16
     assert B.rlda_desc.q.offset == 48 and B.rlda_desc.workspace_bytes.offset == 48 + 10 * 8
+    assert B.rlda_desc.k_scale.offset == 48 + 11 * 8 and B.rlda_desc.v_scale.offset == 48 + 12 * 8
+
+
+def test_e4m3_store_dtype_is_planned_like_bf16():
+    from paper_2512_21450_amd import workloads as wl
+    W = wl.WORKLOADS["vlm7b"]
+    ds = B.make_desc(B.RLDA_BF16_KV8, W.P, W.G, W.Hq, W.Hkv, W.d, W.Lp_cap, W.Ls_cap, W.scale)
+    ref = B.make_desc(B.RLDA_BF16, W.P, W.G, W.Hq, W.Hkv, W.d, W.Lp_cap, W.Ls_cap, W.scale)
+    assert B.rl_decode_attn_plan(ds) == B.RLDA_ALGO_SHARED
+    assert B.rl_decode_attn_workspace_bytes(ds) == B.rl_decode_attn_workspace_bytes(ref)   # partials do not depend on the store
+    assert B.rl_decode_attn_plan(good(dtype=B.RLDA_BF16_KV8, d=64)) == B.RLDA_ALGO_SIMPLE
+    assert B.rl_decode_attn_plan(good(dtype=3)) == B.RLDA_ERR_UNSUPPORTED
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -126,9 +138,10 @@ def good_paged(**kw):
 
 
 def test_paged_descriptor_layout_matches_the_header():
-    # 13 four-byte fields, padding to 8, 11 pointers, pointer + size_t
-    assert ctypes.sizeof(B.rlda_paged_desc) == 56 + 11 * 8 + 16
+    # 13 four-byte fields, padding to 8, 11 pointers, pointer + size_t, the two scale pointers
+    assert ctypes.sizeof(B.rlda_paged_desc) == 56 + 11 * 8 + 16 + 16
     assert B.rlda_paged_desc.q.offset == 56 and B.rlda_paged_desc.workspace_bytes.offset == 56 + 12 * 8
+    assert B.rlda_paged_desc.k_scale.offset == 56 + 13 * 8 and B.rlda_paged_desc.v_scale.offset == 56 + 14 * 8
 
 
 @pytest.mark.parametrize("kw,code", [

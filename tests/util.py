@@ -24,13 +24,15 @@ def to_device(x, device="cuda:0"):
 def oracle(x, scale, G, **kw):
     from oracle import ref
     return ref.decode_attn_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"],
-                               x["k_suffix"], x["v_suffix"], x["suffix_lens"], scale, G, **kw)
+                               x["k_suffix"], x["v_suffix"], x["suffix_lens"], scale, G,
+                               k_scale=x.get("k_scale"), v_scale=x.get("v_scale"), **kw)
 
 
 def gpu_run(t, scale, G, **kw):
     from paper_2512_21450_amd import binding
     return binding.rl_decode_attn(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"],
-                                  t["k_suffix"], t["v_suffix"], t["suffix_lens"], scale, G, **kw)
+                                  t["k_suffix"], t["v_suffix"], t["suffix_lens"], scale, G,
+                                  k_scale=t.get("k_scale"), v_scale=t.get("v_scale"), **kw)
 
 
 def compare(out, lse, ref_out, ref_lse, dtype, what=""):
@@ -68,11 +70,12 @@ def random_case(seed, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, dtype="bf16", plens=None
 def oracle_paged(y, scale, G, active=None, **kw):
     from oracle import ref
     return ref.decode_attn_paged_ref(y["q"], y["k_prefix"], y["v_prefix"], y["prefix_lens"], y["k_pages"],
-                                     y["v_pages"], y["block_table"], y["suffix_lens"], active, scale, G, **kw)
+                                     y["v_pages"], y["block_table"], y["suffix_lens"], active, scale, G,
+                                     k_scale=y.get("k_scale"), v_scale=y.get("v_scale"), **kw)
 
 
 def gpu_run_paged(t, scale, G, active=None, **kw):
     from paper_2512_21450_amd import binding
     return binding.rl_decode_attn_paged(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_pages"],
                                         t["v_pages"], t["block_table"], t["suffix_lens"], scale, G,
-                                        seq_active=active, **kw)
+                                        seq_active=active, k_scale=t.get("k_scale"), v_scale=t.get("v_scale"), **kw)
