@@ -147,3 +147,68 @@ def test_bf16_rounding_is_nearest_even():
     got = _narrow(vals, like)
     assert got.tolist() == [0x3F80, 0x3F80, 0x3F82, 0x3F81, 0xC020]
     assert np.array_equal(got, wl.f32_to_bf16_bits(vals.astype(np.float32)))
+
+
+# ---------------------------------------------------------------- e4m3 stores
+def test_e4m3_quantiser_against_the_definition():
+    from oracle import ref
+    from oracle.kv_append_ref import e4m3_round
+    codes = np.arange(256, dtype=np.uint8)
+    vals = ref.e4m3_to_f64(codes)                      # the decoder pinned in test_oracle_kv8_pins.py
+    ok = ~np.isnan(vals)
+    assert np.array_equal(e4m3_round(vals[ok]), codes[ok])            # representable values (and -0) keep their code
+    pos = vals[:0x7F]
+    for i in range(0x7E):                                             # between neighbours: nearest, ties to the even code
+        lo, hi = pos[i], pos[i + 1]
+        mid = (lo + hi) / 2
+        assert e4m3_round(mid) == (i if i % 2 == 0 else i + 1), i
+        assert e4m3_round(-mid) == (i if i % 2 == 0 else i + 1) | 0x80
+        assert e4m3_round(np.nextafter(np.float32(mid), np.float32(0))) == i or np.float32(mid) != mid
+        assert e4m3_round(mid - (hi - lo) / 64) == i and e4m3_round(mid + (hi - lo) / 64) == i + 1
+    assert e4m3_round(448.0) == 0x7E and e4m3_round(449.0) == 0x7E and e4m3_round(1e30) == 0x7E
+    assert e4m3_round(np.inf) == 0x7E and e4m3_round(-np.inf) == 0xFE
+    assert e4m3_round(np.nan) & 0x7F == 0x7F
+    assert e4m3_round(2.0 ** -10) == 0 and e4m3_round(2.0 ** -10 * 1.01) == 1      # half of the smallest subnormal ties to 0
+    assert e4m3_round(0.0) == 0 and e4m3_round(-0.0) == 0x80
+
+
+def test_e4m3_quantiser_against_library_rounding():
+    import torch
+    from oracle.kv_append_ref import e4m3_round
+    rng = np.random.default_rng(3)
+    x = np.concatenate([(rng.standard_normal(200000) * s).astype(np.float32) for s in (0.01, 1.0, 100.0)])
+    x = x[np.abs(x) <= 448]                                            # beyond the range the library does not saturate
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(e4m3_round(x), lib)
+
+
+def test_append_quantises_with_the_head_factor_and_leaves_other_rows_alone():
+    from oracle import ref
+    from oracle.kv_append_ref import e4m3_round
+    x = case(21, dtype="bf16", lens=[0, 4, 5])                         # the third sequence is full (capacity 5)
+    rng = np.random.default_rng(5)
+    x["k_store"] = rng.integers(0, 256, x["k_store"].shape).astype(np.uint8)
+    x["v_store"] = rng.integers(0, 256, x["v_store"].shape).astype(np.uint8)
+    ksc, vsc = np.array([0.01, 0.37], np.float32), np.array([0.02, 0.005], np.float32)
+    q_rot, ks, vs, lens = run(x, k_scale=ksc, v_scale=vsc)
+    assert lens.tolist() == [1, 5, 5] and ks.dtype == np.uint8
+    touched = np.zeros(ks.shape, bool)
+    touched[0, :, 0] = True; touched[1, :, 4] = True
+    assert np.array_equal(ks[~touched], x["k_store"][~touched]) and np.array_equal(vs[~touched], x["v_store"][~touched])
+    v = wl.bf16_bits_to_f32(x["v_new"])
+    for b, n in ((0, 0), (1, 4)):
+        for j in range(2):
+            want = e4m3_round((v[b, j] / vsc[j]).astype(np.float32))
+            assert np.array_equal(vs[b, j, n], want)
+            # dequantised, the stored row is within half an e4m3 step of the value (relative 2^-4 for normal values)
+            back = ref.e4m3_to_f64(vs[b, j, n]) * float(vsc[j])
+            assert np.all(np.abs(back - v[b, j]) <= np.maximum(np.abs(v[b, j]) * 2.0 ** -4, float(vsc[j]) * 2.0 ** -10))
+    # the key row is the rotated key: same rotation as the bf16-store form, quantised from fp32
+    cos, sin = rope_tables(x["positions"], x["inv_freq"], list(x["sections"]))
+    kr = rotate(wl.bf16_bits_to_f32(x["k_new"]).astype(np.float64), cos, sin).astype(np.float32)
+    for j in range(2):
+        assert np.array_equal(ks[0, j, 0], e4m3_round((kr[0, j] / ksc[j]).astype(np.float32)))
+    # factors of one are the default
+    a = run(x)
+    b = run(x, k_scale=np.ones(2, np.float32), v_scale=np.ones(2, np.float32))
+    assert all(np.array_equal(u, w) for u, w in zip(a, b))
