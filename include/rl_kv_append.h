@@ -46,7 +46,8 @@ extern "C" {
 /* All pointers are DEVICE memory, borrowed until the enqueued work has run. */
 typedef struct {
   uint32_t struct_size;         /* = sizeof(rl_kv_append_desc)                                   */
-  int32_t  dtype;               /* element type of q, k_new, v_new and the stores: 0 fp32, 1 bf16 */
+  int32_t  dtype;               /* element type of q, k_new, v_new and the stores: 0 fp32, 1 bf16;
+                                   2: q, k_new, v_new bf16 and the stores e4m3 bytes (see below)  */
   int32_t  B, Hq, Hkv, d;       /* sequences, query heads, KV heads, head dim (64 or 128)        */
   int32_t  Ls_cap;              /* contiguous store: rows per sequence                           */
   int32_t  page_size, max_pages, n_pages;   /* paged store (block_table != NULL); else ignored   */
@@ -61,7 +62,18 @@ typedef struct {
   const int32_t* block_table;   /* [B, max_pages] or NULL                                        */
   int32_t*       suffix_lens;   /* [B]  in: row to write; out: incremented where a row was written */
   const uint8_t* seq_active;    /* [B] or NULL                                                   */
+  const float*   k_scale;       /* [Hkv] dtype 2 only (else ignored): factors of the e4m3 stores, > 0; NULL = 1 */
+  const float*   v_scale;       /* [Hkv] likewise                                                */
 } rl_kv_append_desc;
+
+/*
+ * dtype 2 (the stores of RLDA_BF16_KV8 in rl_decode_attn.h): the appended rows are quantised,
+ *   byte = the e4m3 value nearest to x / factor[j]  (x and the quotient in fp32; ties to the even
+ *          code; magnitudes above 448, infinities included, become 448; NaN becomes 0x7f)
+ * where x is the rotated key as computed in fp32 (not rounded to bf16 first) or the value as
+ * given.  Reading the row back through rl_decode_attn with the same factors gives x to within
+ * half an e4m3 step (relative 2^-4).
+ */
 
 /*
  * Enqueue on `hip_stream` (hipStream_t as void*).  Asynchronous, allocates

@@ -422,6 +422,7 @@ class rl_kv_append_desc(ctypes.Structure):
         ("positions", ctypes.c_void_p), ("inv_freq", ctypes.c_void_p),
         ("k_store", ctypes.c_void_p), ("v_store", ctypes.c_void_p),
         ("block_table", ctypes.c_void_p), ("suffix_lens", ctypes.c_void_p), ("seq_active", ctypes.c_void_p),
+        ("k_scale", ctypes.c_void_p), ("v_scale", ctypes.c_void_p),
     ]
 
 
@@ -446,16 +447,19 @@ def rl_kv_append_rope_raw(desc: rl_kv_append_desc, stream_handle=None) -> int:
 
 
 def kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
-                                block_table=None, seq_active=None) -> rl_kv_append_desc:
+                                block_table=None, seq_active=None, k_scale=None, v_scale=None) -> rl_kv_append_desc:
     """Descriptor over torch device tensors.  ``k_store`` / ``v_store`` are [B, Hkv, Ls_cap, d], or with
-    ``block_table`` the page pools [n_pages, Hkv, page_size, d]."""
+    ``block_table`` the page pools [n_pages, Hkv, page_size, d]; uint8 / float8_e4m3fn stores take e4m3
+    bytes quantised with the factors ``k_scale`` / ``v_scale`` (float32 [Hkv])."""
     import torch
     B, Hq, d = q.shape
     Hkv = k_new.shape[1]
     code = _torch_dtype_code(q)
-    for t in (k_new, v_new, k_store, v_store):
+    for t in (k_new, v_new):
         if _torch_dtype_code(t) != code:
-            raise TypeError("q, k_new, v_new and the stores must share one element type")
+            raise TypeError("q, k_new and v_new must share one element type")
+    if _kv_dtype_code(q, (k_store, v_store), k_scale, v_scale) == RLDA_BF16_KV8:
+        code = 2
     if positions.dtype != torch.int32 or tuple(positions.shape) != (3, B) or inv_freq.dtype != torch.float32:
         raise TypeError("positions must be int32 [3, B] and inv_freq float32 [d/2]")
     if suffix_lens.dtype != torch.int32 or (block_table is not None and block_table.dtype != torch.int32):
@@ -466,7 +470,7 @@ def kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, 
     ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
     kw = dict(q=ptr(q), k_new=ptr(k_new), v_new=ptr(v_new), positions=ptr(positions), inv_freq=ptr(inv_freq),
               k_store=ptr(k_store), v_store=ptr(v_store), block_table=ptr(block_table),
-              suffix_lens=ptr(suffix_lens), seq_active=ptr(seq_active))
+              suffix_lens=ptr(suffix_lens), seq_active=ptr(seq_active), k_scale=ptr(k_scale), v_scale=ptr(v_scale))
     if block_table is None:
         if tuple(k_store.shape[:2]) != (B, Hkv):
             raise ValueError("contiguous store must be [B, Hkv, Ls_cap, d]")
@@ -476,13 +480,13 @@ def kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, 
 
 
 def rl_kv_append_rope(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
-                      block_table=None, seq_active=None, stream=None) -> None:
+                      block_table=None, seq_active=None, stream=None, k_scale=None, v_scale=None) -> None:
     """Rotate q (in place) and k_new, append k / v to the store, increment suffix_lens.  Asynchronous."""
     import torch
     if not q.is_cuda:
         raise RuntimeError("rl_kv_append_rope needs device tensors; there is no CPU path")
     ds = kv_append_desc_from_tensors(q, k_new, v_new, positions, inv_freq, sections, k_store, v_store, suffix_lens,
-                                     block_table, seq_active)
+                                     block_table, seq_active, k_scale, v_scale)
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
     rc = _lib.rl_kv_append_rope(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
     if rc != RLDA_OK:

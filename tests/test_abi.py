@@ -225,8 +225,8 @@ def good_ka(**kw):
 
 
 def test_kv_append_descriptor_layout_and_errors():
-    assert ctypes.sizeof(B.rl_kv_append_desc) == 56 + 10 * 8
-    assert B.rl_kv_append_desc.q.offset == 56
+    assert ctypes.sizeof(B.rl_kv_append_desc) == 56 + 12 * 8          # 10 tensor pointers, the two factor arrays
+    assert B.rl_kv_append_desc.q.offset == 56 and B.rl_kv_append_desc.k_scale.offset == 56 + 10 * 8
     fake = 0x1000
     ptrs = dict(q=fake, k_new=fake, v_new=fake, positions=fake, inv_freq=fake, k_store=fake, v_store=fake, suffix_lens=fake)
     for kw, code in [(dict(d=96), -2), (dict(sections=(16, 24, 23)), -2), (dict(sections=(-1, 41, 24)), -2),

@@ -178,3 +178,95 @@ def test_append_then_attend_loop_in_a_graph(B):
         for i in range(steps):
             assert torch.equal(outs[i], eager[i][0]) and torch.equal(lses[i], eager[i][1]), f"replay {rep} step {i}"
         assert np.array_equal(host(lens_d), lens)
+
+
+# ---------------------------------------------------------------- e4m3 stores
+def codes_close(got, want, what):
+    """e4m3 bytes: identical except where the fp32 quotient sits on a rounding boundary (one code step, rare)."""
+    same = got == want
+    assert same.mean() >= 0.999, f"{what}: only {same.mean():.5f} of the bytes identical"
+    g, w = got[~same].astype(np.int32), want[~same].astype(np.int32)
+    assert ((g & 0x80) == (w & 0x80)).all() and (np.abs((g & 0x7F) - (w & 0x7F)) <= 1).all(), f"{what}: more than one step"
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_e4m3_store_append_then_attend(B, paged):
+    import torch
+    w = wl.scaled(wl.WORKLOADS["vlm7b"], P=4, Ls_cap=512, suffix=("uniform", 500))
+    x = wl.kv_to_e4m3(wl.make_inputs(w))
+    nt = wl.make_new_token(w, x, seed=9)
+    lens = x["suffix_lens"].copy(); lens[3] = 512; lens[6] = 0; lens[8] = 31; lens[9] = 32
+    act = None
+    if paged:
+        full = dict(x); full["suffix_lens"] = np.full(w.B, 512, np.int32)
+        y = wl.to_pages(full, 64, seed=3, poison=False)
+        k0, v0, table = y["k_pages"], y["v_pages"], y["block_table"]
+        act = (np.arange(w.B) % 5 != 2).astype(np.uint8)
+    else:
+        k0, v0, table = x["k_suffix"], x["v_suffix"], None
+    t = {k: dev(v) for k, v in nt.items() if isinstance(v, np.ndarray)}
+    ks, vs, ln = dev(k0), dev(v0), dev(lens)
+    ksc, vsc = dev(x["k_scale"]), dev(x["v_scale"])
+    B.rl_kv_append_rope(t["q"], t["k_new"], t["v_new"], t["positions"], t["inv_freq"], nt["sections"], ks, vs, ln,
+                        block_table=None if table is None else dev(table),
+                        seq_active=None if act is None else torch.from_numpy(act).cuda(), k_scale=ksc, v_scale=vsc)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref, l_ref = kv_append_rope_ref(nt["q"], nt["k_new"], nt["v_new"], nt["positions"], nt["inv_freq"],
+                                                    nt["sections"], k0, v0, lens, block_table=table, seq_active=act,
+                                                    k_scale=x["k_scale"], v_scale=x["v_scale"])
+    assert np.array_equal(host(ln), l_ref)
+    assert (l_ref != lens).sum() >= w.B // 2                       # most sequences did take a row
+    assert np.array_equal(host(vs), v_ref), "value store: the quotient and its rounding are fully specified"
+    close(host(t["q"]), q_ref, "q")
+    gk = host(ks)
+    changed = k_ref != k0
+    assert np.array_equal(gk[~changed], k0[~changed])
+    codes_close(gk, k_ref, "key store")
+    # the attention of the next step reads what the append wrote (its own bytes: parity by the usual bar)
+    from paper_2512_21450_amd import binding
+    tx = util.to_device({k: x[k] for k in ("k_prefix", "v_prefix", "prefix_lens")})
+    if paged:
+        out, lse = binding.rl_decode_attn_paged(t["q"], tx["k_prefix"], tx["v_prefix"], tx["prefix_lens"], ks, vs,
+                                                dev(table), ln, w.scale, w.G, seq_active=torch.from_numpy(act).cuda(),
+                                                k_scale=ksc, v_scale=vsc)
+        z = dict(q=host(t["q"]), k_prefix=x["k_prefix"], v_prefix=x["v_prefix"], prefix_lens=x["prefix_lens"],
+                 k_pages=gk, v_pages=host(vs), block_table=table, suffix_lens=host(ln), k_scale=x["k_scale"],
+                 v_scale=x["v_scale"])
+        ro, rl = util.oracle_paged(z, w.scale, w.G, active=act)
+    else:
+        out, lse = binding.rl_decode_attn(t["q"], tx["k_prefix"], tx["v_prefix"], tx["prefix_lens"], ks, vs, ln,
+                                          w.scale, w.G, k_scale=ksc, v_scale=vsc)
+        z = dict(q=host(t["q"]), k_prefix=x["k_prefix"], v_prefix=x["v_prefix"], prefix_lens=x["prefix_lens"],
+                 k_suffix=gk, v_suffix=host(vs), suffix_lens=host(ln), k_scale=x["k_scale"], v_scale=x["v_scale"])
+        ro, rl = util.oracle(z, w.scale, w.G)
+    util.compare(out, lse, ro, rl, "bf16", f"attend after e4m3 append (paged={paged})")
+
+
+def test_e4m3_quantiser_on_chosen_values(B):
+    """Values placed on and next to every rounding boundary, through the value path (a plain quotient)."""
+    import torch
+    from oracle import ref
+    from oracle.kv_append_ref import e4m3_round
+    tab = ref.e4m3_to_f64(np.arange(0x7F))
+    mids = (tab[:-1] + tab[1:]) / 2
+    vals = np.concatenate([tab, mids, mids * (1 + 2.0 ** -8), mids * (1 - 2.0 ** -8), [448.0, 460.0, 1e4, 3e38, 0.0]])
+    vals = np.concatenate([vals, -vals]).astype(np.float32)
+    vals = wl.bf16_bits_to_f32(wl.f32_to_bf16_bits(vals))             # the value path takes bf16 inputs
+    n = -(-vals.size // 128) * 128
+    v = np.zeros(n, np.float32); v[:vals.size] = vals
+    Bn = n // 128
+    v_new = wl.f32_to_bf16_bits(v.reshape(Bn, 1, 128))
+    z = lambda *s: torch.zeros(s, dtype=torch.bfloat16, device="cuda")
+    vs = torch.zeros((Bn, 1, 1, 128), dtype=torch.uint8, device="cuda")
+    ks = torch.zeros_like(vs)
+    lens = torch.zeros(Bn, dtype=torch.int32, device="cuda")
+    for factor in (1.0, 0.75, 3.0):
+        lens.zero_()
+        B.rl_kv_append_rope(z(Bn, 1, 128), z(Bn, 1, 128), dev(v_new), torch.zeros((3, Bn), dtype=torch.int32, device="cuda"),
+                            dev(wl.rope_inv_freq(128)), wl.mrope_sections(128), ks, vs, lens,
+                            v_scale=torch.tensor([factor], dtype=torch.float32, device="cuda"))
+        torch.cuda.synchronize()
+        with np.errstate(over="ignore"):                              # 3e38 / 0.75 overflows to inf, which saturates
+            want = e4m3_round((wl.bf16_bits_to_f32(v_new) / np.float32(factor)).astype(np.float32)).reshape(Bn, 1, 1, 128)
+        assert np.array_equal(vs.cpu().numpy(), want), factor
+        assert (ks.cpu().numpy() == 0).all()                          # zero keys rotate to zero
