@@ -77,8 +77,10 @@ def main():
                     help="fraction of sequences marked finished (paged store only)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob"],
-                    help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel")
+    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss"],
+                    help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel; "
+                         "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens")
+    ap.add_argument("--tokens", type=int, default=1024, help="policy_loss: token capacity per sequence")
     ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
     ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
     ap.add_argument("--no-ref", action="store_true", help="token_logprob: no reference logits (no KL)")
@@ -97,6 +99,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.op == "token_logprob":
         return bench_token_logprob(args, torch, B, wl, dev)
+    if args.op == "policy_loss":
+        return bench_policy_loss(args, torch, B, wl, dev)
     w = wl.WORKLOADS[args.workload]
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
@@ -367,6 +371,75 @@ def bench_token_logprob(args, torch, B, wl, dev):
         "cpu_baseline": {"value": len(rows) / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
                          "sample": f"{len(rows)} of {n} rows, {c1 - c0:.2f} s"},
         "parity": {"ok": ok, "max_abs_err": errs},
+    }))
+    if not ok:
+        sys.exit(1)
+
+
+def bench_policy_loss(args, torch, B, wl, dev):
+    """One step = rl_group_advantage + rl_policy_loss (with KL and entropy terms and the gradient) over
+    [rows, tokens] per-token tensors with lognormal response lengths."""
+    n, T, G = args.rows, args.tokens, 16
+    n -= n % G
+    x = wl.make_rollout_tokens(n, T, G, seed=4001, lens=("lognormal", 200.0, 1.0))
+    t = {k: torch.from_numpy(v).to(dev) for k, v in x.items() if isinstance(v, np.ndarray)}
+    stats = torch.empty(8, dtype=torch.float32, device=dev)
+    grad = torch.empty((n, T), dtype=torch.float32, device=dev)
+    rewards = torch.empty(n, dtype=torch.float32, device=dev)
+    adv = torch.empty(n, dtype=torch.float32, device=dev)
+    da = B.make_group_advantage_desc(n // G, G, x["metrics"].shape[0], metrics=t["metrics"].data_ptr(),
+                                     weights=t["weights"].data_ptr(), rewards=rewards.data_ptr(), advantages=adv.data_ptr())
+    dl = B.policy_loss_desc_from_tensors(t["logprob"], t["old_logprob"], adv, t["lens"], 0.2, 0.28, stats, t["kl"],
+                                         t["entropy"], grad, 0.04, 0.01, agg=B.RL_AGG_SEQ_MEAN)
+    ws = torch.empty(max(B.rl_policy_loss_workspace_bytes(dl), 256), dtype=torch.uint8, device=dev)
+    dl.workspace, dl.workspace_bytes = ws.data_ptr(), ws.numel()
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = B.rl_group_advantage_raw(da, stream.cuda_stream) or B.rl_policy_loss_raw(dl, stream.cuda_stream)
+        if rc != 0:
+            raise B.RldaError(rc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    call_us = e0.elapsed_time(e1) * 1e3 / args.steps
+    valid = int(np.clip(x["lens"], 0, T).sum())
+    nbytes = valid * 4 * 4 + n * T * 4 + n * 4 * 4          # four input arrays on valid tokens, the gradient rows, per-sequence vectors
+
+    from oracle.policy_loss_ref import AGG_SEQ_MEAN, group_advantage_ref, policy_loss_ref
+    c0 = time.perf_counter()
+    _, a_ref = group_advantage_ref(x["metrics"], x["weights"], G)
+    r = policy_loss_ref(x["logprob"], x["old_logprob"], a_ref.astype(np.float32), x["lens"], 0.2, 0.28, kl=x["kl"],
+                        entropy=x["entropy"], beta_kl=0.04, beta_ent=0.01, agg=AGG_SEQ_MEAN)
+    c1 = time.perf_counter()
+    got = dict(zip(B.POLICY_LOSS_STATS, stats.cpu().numpy().astype(np.float64)))
+    errs = {k: abs(got[k] - r[k]) for k in ("loss", "pg", "kl", "entropy")}
+    ok = all(errs[k] <= 1e-4 * abs(r[k]) + 1e-6 for k in errs) and got["n_tokens"] == r["n_tokens"]
+    achieved = nbytes / (call_us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "policy-loss tokens per second and achieved HBM GB/s", "value": valid / (ms_per_step * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"policy_loss: {n} sequences x {T} tokens (G={G}), lognormal lengths, {valid} valid tokens, "
+                               "KL + entropy terms, gradient written"},
+        "algorithmic_bytes": nbytes,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "group_advantage_kernel + policy_count_kernel + policy_loss_kernel + policy_loss_reduce_kernel",
+                     "call_us_mean": call_us},
+        "cpu_baseline": {"value": valid / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                         "sample": f"the whole batch, one pass, {c1 - c0:.2f} s"},
+        "parity": {"ok": bool(ok), "abs_err": errs},
     }))
     if not ok:
         sys.exit(1)

@@ -491,3 +491,144 @@ def rl_kv_append_rope(q, k_new, v_new, positions, inv_freq, sections, k_store, v
     rc = _lib.rl_kv_append_rope(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
     if rc != RLDA_OK:
         raise RldaError(rc)
+
+
+# ---------------------------------------------------------------- rl_policy_loss.h
+RL_ADV_GROUP_NORM, RL_ADV_GROUP_CENTER, RL_ADV_LEAVE_ONE_OUT = 0, 1, 2
+RL_PG_PPO_CLIP, RL_PG_AS_PRINTED = 0, 1
+RL_AGG_TOKEN_MEAN, RL_AGG_SEQ_MEAN = 0, 1
+POLICY_LOSS_STATS = ("loss", "pg", "kl", "entropy", "clip_frac", "ratio_mean", "approx_kl", "n_tokens")
+
+
+class rl_group_advantage_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("mode", ctypes.c_int32),
+        ("P", ctypes.c_int32), ("G", ctypes.c_int32),
+        ("n_metrics", ctypes.c_int32),
+        ("unbiased", ctypes.c_int32),
+        ("eps", ctypes.c_float),
+        ("metrics", ctypes.c_void_p), ("weights", ctypes.c_void_p),
+        ("rewards", ctypes.c_void_p), ("advantages", ctypes.c_void_p),
+    ]
+
+
+class rl_policy_loss_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("form", ctypes.c_int32), ("agg", ctypes.c_int32),
+        ("B", ctypes.c_int32), ("T", ctypes.c_int32),
+        ("row_stride", ctypes.c_int64),
+        ("clip_low", ctypes.c_float), ("clip_high", ctypes.c_float),
+        ("beta_kl", ctypes.c_float), ("beta_ent", ctypes.c_float),
+        ("logprob", ctypes.c_void_p), ("old_logprob", ctypes.c_void_p), ("advantages", ctypes.c_void_p),
+        ("kl", ctypes.c_void_p), ("entropy", ctypes.c_void_p), ("lens", ctypes.c_void_p),
+        ("grad_logprob", ctypes.c_void_p), ("stats", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+_lib.rl_group_advantage.restype = ctypes.c_int
+_lib.rl_group_advantage.argtypes = [ctypes.POINTER(rl_group_advantage_desc), ctypes.c_void_p]
+_lib.rl_policy_loss.restype = ctypes.c_int
+_lib.rl_policy_loss.argtypes = [ctypes.POINTER(rl_policy_loss_desc), ctypes.c_void_p]
+_lib.rl_policy_loss_workspace_bytes.restype = ctypes.c_size_t
+_lib.rl_policy_loss_workspace_bytes.argtypes = [ctypes.POINTER(rl_policy_loss_desc)]
+
+
+def make_group_advantage_desc(P, G, n_metrics, mode=RL_ADV_GROUP_NORM, eps=1e-6, unbiased=1, **ptrs):
+    ds = rl_group_advantage_desc()
+    ds.struct_size = ctypes.sizeof(rl_group_advantage_desc)
+    ds.mode, ds.P, ds.G, ds.n_metrics, ds.unbiased, ds.eps = mode, P, G, n_metrics, unbiased, eps
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_group_advantage_raw(desc: rl_group_advantage_desc, stream_handle=None) -> int:
+    return _lib.rl_group_advantage(ctypes.byref(desc), stream_handle)
+
+
+def rl_group_advantage(metrics, weights, G, mode=RL_ADV_GROUP_NORM, eps=1e-6, unbiased=True, stream=None):
+    """metrics [M, B], weights [M] (float32 device tensors) -> (rewards [B], advantages [B]).  Asynchronous."""
+    import torch
+    if not metrics.is_cuda:
+        raise RuntimeError("rl_group_advantage needs device tensors; there is no CPU path")
+    if metrics.dtype != torch.float32 or weights.dtype != torch.float32 or not metrics.is_contiguous():
+        raise TypeError("metrics / weights must be contiguous float32")
+    M, Bn = metrics.shape
+    if Bn % G or weights.numel() != M:
+        raise ValueError("inconsistent shapes")
+    rewards = torch.empty(Bn, dtype=torch.float32, device=metrics.device)
+    adv = torch.empty(Bn, dtype=torch.float32, device=metrics.device)
+    ds = make_group_advantage_desc(Bn // G, G, M, mode, float(eps), int(bool(unbiased)), metrics=metrics.data_ptr(),
+                                   weights=weights.data_ptr(), rewards=rewards.data_ptr(), advantages=adv.data_ptr())
+    s = stream if stream is not None else torch.cuda.current_stream(metrics.device)
+    rc = _lib.rl_group_advantage(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return rewards, adv
+
+
+def make_policy_loss_desc(B, T, row_stride, clip_low, clip_high, beta_kl=0.0, beta_ent=0.0, form=RL_PG_PPO_CLIP,
+                          agg=RL_AGG_TOKEN_MEAN, **ptrs) -> rl_policy_loss_desc:
+    ds = rl_policy_loss_desc()
+    ds.struct_size = ctypes.sizeof(rl_policy_loss_desc)
+    ds.form, ds.agg, ds.B, ds.T, ds.row_stride = form, agg, B, T, row_stride
+    ds.clip_low, ds.clip_high, ds.beta_kl, ds.beta_ent = clip_low, clip_high, beta_kl, beta_ent
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_policy_loss_workspace_bytes(desc: rl_policy_loss_desc) -> int:
+    return _lib.rl_policy_loss_workspace_bytes(ctypes.byref(desc))
+
+
+def rl_policy_loss_raw(desc: rl_policy_loss_desc, stream_handle=None) -> int:
+    return _lib.rl_policy_loss(ctypes.byref(desc), stream_handle)
+
+
+def policy_loss_desc_from_tensors(logprob, old_logprob, advantages, lens, clip_low, clip_high, stats, kl=None,
+                                  entropy=None, grad=None, beta_kl=0.0, beta_ent=0.0, form=RL_PG_PPO_CLIP,
+                                  agg=RL_AGG_TOKEN_MEAN, workspace=None) -> rl_policy_loss_desc:
+    """Descriptor over torch device tensors; the [B, T] tensors may be row-strided views sharing one stride."""
+    import torch
+    Bn, T = logprob.shape
+    stride = logprob.stride(0) if Bn > 1 else max(T, 1)
+    for t in (logprob, old_logprob, kl, entropy, grad):
+        if t is None:
+            continue
+        if t.dtype != torch.float32 or tuple(t.shape) != (Bn, T) or (T > 1 and t.stride(1) != 1) or \
+                (Bn > 1 and t.stride(0) != stride):
+            raise TypeError("the [B, T] tensors must be float32 with unit column stride and one common row stride")
+    if advantages.dtype != torch.float32 or lens.dtype != torch.int32 or stats.dtype != torch.float32 or stats.numel() < 8:
+        raise TypeError("advantages float32 [B], lens int32 [B], stats float32 [8]")
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    return make_policy_loss_desc(Bn, T, stride, float(clip_low), float(clip_high), float(beta_kl), float(beta_ent), form,
+                                 agg, logprob=ptr(logprob), old_logprob=ptr(old_logprob), advantages=ptr(advantages),
+                                 kl=ptr(kl), entropy=ptr(entropy), lens=ptr(lens), grad_logprob=ptr(grad),
+                                 stats=ptr(stats), workspace=ptr(workspace),
+                                 workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+
+
+def rl_policy_loss(logprob, old_logprob, advantages, lens, clip_low, clip_high, kl=None, entropy=None, beta_kl=0.0,
+                   beta_ent=0.0, form=RL_PG_PPO_CLIP, agg=RL_AGG_TOKEN_MEAN, want_grad=True, workspace=None, stream=None):
+    """Clipped policy loss over [B, T] per-token tensors; returns (stats [8] device tensor in the order of
+    POLICY_LOSS_STATS, grad_logprob [B, T] or None).  Asynchronous."""
+    import torch
+    if not logprob.is_cuda:
+        raise RuntimeError("rl_policy_loss needs device tensors; there is no CPU path")
+    stats = torch.empty(8, dtype=torch.float32, device=logprob.device)
+    grad = torch.empty_like(logprob) if want_grad else None
+    ds = policy_loss_desc_from_tensors(logprob, old_logprob, advantages, lens, clip_low, clip_high, stats, kl, entropy,
+                                       grad, beta_kl, beta_ent, form, agg, workspace)
+    if workspace is None:
+        need = rl_policy_loss_workspace_bytes(ds)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=logprob.device)
+        ds.workspace, ds.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    s = stream if stream is not None else torch.cuda.current_stream(logprob.device)
+    rc = _lib.rl_policy_loss(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return stats, grad

@@ -12,7 +12,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librl_decode_attn.so")
-SOURCES = ["rlda_api.hip", "rlda_simple.hip", "rlda_shared.hip", "rlda_token_logprob.hip", "rlda_kv_append.hip"]
+SOURCES = ["rlda_api.hip", "rlda_simple.hip", "rlda_shared.hip", "rlda_token_logprob.hip", "rlda_kv_append.hip",
+           "rlda_policy_loss.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

@@ -283,3 +283,23 @@ def make_new_token(w: Workload, x: dict, seed: int) -> dict:
     p3[2, img] = rng.integers(0, 48, int(img.sum()))
     return {"q": t(20, (w.B, w.Hq, w.d)), "k_new": t(21, (w.B, w.Hkv, w.d)), "v_new": t(22, (w.B, w.Hkv, w.d)),
             "positions": p3, "inv_freq": rope_inv_freq(w.d), "sections": mrope_sections(w.d)}
+
+
+# ---- per-token tensors of a finished rollout batch (for the advantage / policy-loss arithmetic) ----------
+def make_rollout_tokens(B: int, T: int, G: int, seed: int, n_metrics: int = 2, drift: float = 0.15,
+                        lens: tuple = ("lognormal", 300.0, 1.0)) -> dict:
+    """Seeded stand-in for what a rollout hands to the policy update: response lengths, the behaviour
+    policy's log-prob of every sampled token (negative, a few nats), the target policy's (the former plus a
+    small drift, as after a few optimiser steps), per-token KL and entropy (positive), and per-trajectory
+    reward metrics (a 0/1 accuracy-like metric and a format-like one in [0, 1])."""
+    rng = np.random.default_rng(seed)
+    old = -np.abs(rng.standard_normal((B, T), dtype=np.float32)) * 1.5 - 0.01
+    lp = (old + drift * rng.standard_normal((B, T), dtype=np.float32)).astype(np.float32)
+    metrics = np.empty((n_metrics, B), np.float32)
+    metrics[0] = (rng.random(B) < 0.4).astype(np.float32)
+    for m in range(1, n_metrics):
+        metrics[m] = rng.random(B).astype(np.float32)
+    return dict(logprob=lp, old_logprob=old, lens=_draw_lens(rng, lens, B, T),
+                kl=np.abs(rng.standard_normal((B, T), dtype=np.float32)) * 0.05,
+                entropy=np.abs(rng.standard_normal((B, T), dtype=np.float32)) + 0.1,
+                metrics=metrics, weights=np.array([1.0] + [0.5] * (n_metrics - 1), np.float32), G=G)

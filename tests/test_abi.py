@@ -239,3 +239,44 @@ def test_kv_append_descriptor_layout_and_errors():
     ds = good_ka(**ptrs); ds.struct_size = 16
     assert B.rl_kv_append_rope_raw(ds) == -4
     assert B._lib.rl_kv_append_rope(None, None) == -1
+
+
+# ---------------------------------------------------------------- rl_policy_loss.h
+def good_pl(**kw):
+    args = dict(B=4, T=16, row_stride=16, clip_low=0.2, clip_high=0.2)
+    args.update(kw)
+    return B.make_policy_loss_desc(**args)
+
+
+def test_policy_loss_descriptor_layout_and_errors():
+    assert ctypes.sizeof(B.rl_policy_loss_desc) == 48 + 8 * 8 + 16 and B.rl_policy_loss_desc.logprob.offset == 48
+    assert ctypes.sizeof(B.rl_group_advantage_desc) == 32 + 4 * 8 and B.rl_group_advantage_desc.metrics.offset == 32
+    fake = 0x1000
+    full = dict(logprob=fake, old_logprob=fake, advantages=fake, lens=fake, stats=fake, workspace=0x1000, workspace_bytes=1 << 20)
+    for kw, code in [(dict(form=3), -2), (dict(agg=2), -2), (dict(row_stride=8), -2), (dict(B=-1), -1), (dict(T=-2), -1),
+                     (dict(clip_low=-0.1), -1), (dict(clip_high=float("nan")), -1)]:
+        ds = good_pl(**full, **kw)
+        assert B.rl_policy_loss_raw(ds) == code, kw
+        assert B.rl_policy_loss_workspace_bytes(ds) == 0
+    for missing in ("logprob", "old_logprob", "advantages", "lens", "stats"):
+        assert B.rl_policy_loss_raw(good_pl(**{k: v for k, v in full.items() if k != missing})) == -1, missing
+    assert B.rl_policy_loss_workspace_bytes(good_pl()) == 256 + 4 * 32
+    assert B.rl_policy_loss_raw(good_pl(**{**full, "workspace_bytes": 64})) == -3
+    assert B.rl_policy_loss_raw(good_pl(**{**full, "workspace": 0x1010})) == -3          # not 256-byte aligned
+    ds = good_pl(**full); ds.struct_size = 12
+    assert B.rl_policy_loss_raw(ds) == -4
+    assert B._lib.rl_policy_loss(None, None) == -1 and B._lib.rl_policy_loss_workspace_bytes(None) == 0
+
+
+def test_group_advantage_argument_checks():
+    fake = 0x1000
+    ok = dict(metrics=fake, weights=fake, advantages=fake)
+    for kw, code in [(dict(mode=5), -2), (dict(G=1025), -2), (dict(n_metrics=0), -2), (dict(n_metrics=65), -2),
+                     (dict(P=-1), -1), (dict(eps=-1.0), -1)]:
+        args = dict(P=2, G=4, n_metrics=1); args.update(kw)
+        assert B.rl_group_advantage_raw(B.make_group_advantage_desc(**args, **ok)) == code, kw
+    assert B.rl_group_advantage_raw(B.make_group_advantage_desc(2, 4, 1)) == -1              # null tensors
+    assert B.rl_group_advantage_raw(B.make_group_advantage_desc(0, 4, 1)) == 0               # empty batch
+    ds = B.make_group_advantage_desc(2, 4, 1, **ok); ds.struct_size = 8
+    assert B.rl_group_advantage_raw(ds) == -4
+    assert B._lib.rl_group_advantage(None, None) == -1
