@@ -32,9 +32,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # valid for the workload and the kernel sources the counters were taken on.
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "7a8d71008b417924e570daa70443f179dd4ff5aac58fa3edbfbf8624164f8772",
-    "fetch_bytes": 623715708,
-    "write_bytes": 9339956,
+    "csrc_sha256": "cc4fd391478d910bf41c99bf5f064c37d70eb198045aedd7631695cdd7b21473",
+    "fetch_bytes": 623801353,
+    "write_bytes": 9339888,
 }
 
 
