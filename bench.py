@@ -77,9 +77,10 @@ def main():
                     help="fraction of sequences marked finished (paged store only)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss"],
+    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss", "prefill"],
                     help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel; "
-                         "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens")
+                         "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens; "
+                         "prefill: causal attention of the workload's prompts over themselves")
     ap.add_argument("--tokens", type=int, default=1024, help="policy_loss: token capacity per sequence")
     ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
     ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
@@ -101,6 +102,8 @@ def main():
         return bench_token_logprob(args, torch, B, wl, dev)
     if args.op == "policy_loss":
         return bench_policy_loss(args, torch, B, wl, dev)
+    if args.op == "prefill":
+        return bench_prefill(args, torch, B, wl, dev)
     w = wl.WORKLOADS[args.workload]
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
@@ -371,6 +374,74 @@ def bench_token_logprob(args, torch, B, wl, dev):
         "cpu_baseline": {"value": len(rows) / (c1 - c0), "unit": "tokens/s", "cores": 1, "kind": "oracle",
                          "sample": f"{len(rows)} of {n} rows, {c1 - c0:.2f} s"},
         "parity": {"ok": ok, "max_abs_err": errs},
+    }))
+    if not ok:
+        sys.exit(1)
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # dense bf16 matrix-core peak of MI355X
+
+
+def bench_prefill(args, torch, B, wl, dev):
+    """One step = rl_prefill_attn over the prompts of --workload (prefix K/V, lengths and a query per token)."""
+    w = wl.WORKLOADS[args.workload]
+    if w.dtype != "bf16" or w.d != 128:
+        sys.exit("bench.py: --op prefill needs a bf16, d = 128 workload")
+    rng = np.random.default_rng(w.seed)
+    lens = wl._draw_lens(rng, w.prefix, w.P, w.Lp_cap)
+    k = wl._normal_tensor(w.seed, 1, (w.P, w.Hkv, w.Lp_cap, w.d), "bf16", 1.0, 16)
+    v = wl._normal_tensor(w.seed, 2, (w.P, w.Hkv, w.Lp_cap, w.d), "bf16", 1.0, 16)
+    q = wl._normal_tensor(w.seed, 5, (w.P, w.Lp_cap, w.Hq, w.d), "bf16", w.q_gain, 16)
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+    tq, tk, tv, tl = to_dev(q), to_dev(k), to_dev(v), torch.from_numpy(lens).to(dev)
+    out = torch.zeros((w.P, w.Lp_cap, w.Hq, w.d), dtype=torch.float32, device=dev)
+    lse = torch.zeros((w.P, w.Lp_cap, w.Hq), dtype=torch.float32, device=dev)
+    ds = B.prefill_desc_from_tensors(tq, tk, tv, tl, w.scale, out, lse)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = B.rl_prefill_attn_raw(ds, stream.cuda_stream)
+        if rc != 0:
+            raise B.RldaError(rc)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for _ in range(args.steps):
+        step()
+    e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    call_us = e0.elapsed_time(e1) * 1e3 / args.steps
+    L = lens.astype(np.int64)
+    flops = int((4 * w.d * w.Hq * (L * (L + 1) // 2)).sum())          # 2 d per (query, visible key) pair for QK^T, 2 d for PV
+    tokens = int(L.sum())
+
+    from oracle.prefill_ref import prefill_attn_ref
+    c0 = time.perf_counter()
+    ro, rl = prefill_attn_ref(q[:1], k[:1], v[:1], lens[:1], w.scale)
+    c1 = time.perf_counter()
+    o, l = out[0].cpu().numpy().astype(np.float64), lse[0].cpu().numpy().astype(np.float64)
+    n0 = int(lens[0])
+    err_o, err_l = float(np.abs(o[:n0] - ro[0, :n0]).max()), float(np.abs(l[:n0] - rl[0, :n0]).max())
+    ok = err_o <= 1e-2 and err_l <= 1e-3
+    achieved = flops / (call_us * 1e-6) / 1e12
+    print(json.dumps({
+        "metric": "prefill-attention prompt tokens per second and achieved matrix-core TFLOP/s", "value": tokens / (ms_per_step * 1e-3),
+        "unit": "prompt-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"prefill of {w.name}: {w.P} prompts, mean length {L.mean():.0f}, {w.Hq}/{w.Hkv} heads, d={w.d}"},
+        "algorithmic_flops": flops,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None, "kernel": "prefill_kernel",
+                     "kernel_us_mean": call_us},
+        "cpu_baseline": {"value": n0 / (c1 - c0), "unit": "prompt-tokens/s", "cores": 1, "kind": "oracle",
+                         "sample": f"prompt 0 of {w.P} ({n0} tokens, all heads), {c1 - c0:.2f} s"},
+        "parity": {"ok": bool(ok), "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": n0 * w.Hq},
     }))
     if not ok:
         sys.exit(1)

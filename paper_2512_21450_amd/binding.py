@@ -632,3 +632,72 @@ def rl_policy_loss(logprob, old_logprob, advantages, lens, clip_low, clip_high, 
     if rc != RLDA_OK:
         raise RldaError(rc)
     return stats, grad
+
+
+# ---------------------------------------------------------------- rl_prefill_attn.h
+class rl_prefill_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("P", ctypes.c_int32),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("Lp_cap", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("lens", ctypes.c_void_p),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+    ]
+
+
+_lib.rl_prefill_attn.restype = ctypes.c_int
+_lib.rl_prefill_attn.argtypes = [ctypes.POINTER(rl_prefill_desc), ctypes.c_void_p]
+
+
+def make_prefill_desc(dtype, P, Hq, Hkv, d, Lp_cap, scale, **ptrs) -> rl_prefill_desc:
+    ds = rl_prefill_desc()
+    ds.struct_size = ctypes.sizeof(rl_prefill_desc)
+    ds.dtype, ds.P, ds.Hq, ds.Hkv, ds.d, ds.Lp_cap, ds.scale = dtype, P, Hq, Hkv, d, Lp_cap, scale
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_prefill_attn_raw(desc: rl_prefill_desc, stream_handle=None) -> int:
+    return _lib.rl_prefill_attn(ctypes.byref(desc), stream_handle)
+
+
+def prefill_desc_from_tensors(q, k, v, lens, scale, out, lse=None) -> rl_prefill_desc:
+    import torch
+    P, Lc, Hq, d = q.shape
+    Hkv = k.shape[1]
+    if tuple(k.shape) != (P, Hkv, Lc, d) or k.shape != v.shape or tuple(out.shape) != (P, Lc, Hq, d):
+        raise ValueError("q / out are [P, L_cap, Hq, d], k / v are [P, Hkv, L_cap, d]")
+    if lens.dtype != torch.int32 or out.dtype != torch.float32 or (lse is not None and lse.dtype != torch.float32):
+        raise TypeError("lens int32, out / lse float32")
+    for t in (q, k, v, lens, out):
+        if not t.is_contiguous():
+            raise ValueError("tensors must be contiguous")
+    code = _torch_dtype_code(q)
+    if _torch_dtype_code(k) != code or _torch_dtype_code(v) != code:
+        raise TypeError("q/k/v dtypes differ")
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    return make_prefill_desc(code, P, Hq, Hkv, d, Lc, float(scale), q=ptr(q), k=ptr(k), v=ptr(v), lens=ptr(lens),
+                             out=ptr(out), lse=ptr(lse))
+
+
+def rl_prefill_attn(q, k, v, lens, scale, out=None, lse=None, stream=None):
+    """Causal attention of every prompt over itself; returns (out [P, L_cap, Hq, d], lse [P, L_cap, Hq]) fp32.
+    Rows at positions >= lens[p] are left as they were (zero when the outputs are allocated here)."""
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_prefill_attn needs device tensors; there is no CPU path")
+    P, Lc, Hq, d = q.shape
+    if out is None:
+        out = torch.zeros((P, Lc, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.zeros((P, Lc, Hq), dtype=torch.float32, device=q.device)
+    ds = prefill_desc_from_tensors(q, k, v, lens, scale, out, lse)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_prefill_attn(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse

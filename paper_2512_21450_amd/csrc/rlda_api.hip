@@ -3,6 +3,7 @@
 // without a GPU; only rl_decode_attn / rl_lse_combine touch the HIP runtime.
 #include "rlda_internal.h"
 #include "rlda_sched.h"
+#include "../../include/rl_prefill_attn.h"
 
 #include <vector>
 
@@ -233,3 +234,20 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
 }
 
 }  // extern "C"
+
+extern "C" int rl_prefill_attn(const rl_prefill_desc* d, void* hip_stream) {
+  if (!d) return RLDA_ERR_INVALID;
+  if (d->struct_size != sizeof(rl_prefill_desc)) return RLDA_ERR_STRUCT_SIZE;
+  if (d->P < 0 || d->Hq <= 0 || d->Hkv <= 0 || d->d <= 0 || d->Lp_cap < 0) return RLDA_ERR_INVALID;
+  if (!rlda::prefill_supported(d->dtype, d->Hq, d->Hkv, d->d)) return RLDA_ERR_UNSUPPORTED;
+  const int qb = 64 / (d->Hq / d->Hkv);
+  if ((int64_t)((d->Lp_cap + qb - 1) / qb) * d->P * d->Hkv > 0x7fffffffLL) return RLDA_ERR_UNSUPPORTED;
+  if ((int64_t)d->Lp_cap * d->Hq * 256 >= (int64_t)1 << 40) return RLDA_ERR_UNSUPPORTED;
+  if (d->P == 0 || d->Lp_cap == 0) return RLDA_OK;
+  if (!d->q || !d->k || !d->v || !d->lens || !d->out) return RLDA_ERR_INVALID;
+  const hipError_t e = rlda::launch_prefill(d->q, d->k, d->v, d->lens, d->out, d->lse, d->P, d->Hq, d->Hkv, d->Lp_cap,
+                                            d->scale, static_cast<hipStream_t>(hip_stream));
+  g_last_hip_error = e;
+  return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
+}
+

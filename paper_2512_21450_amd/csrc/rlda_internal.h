@@ -42,6 +42,11 @@ size_t shared_workspace_bytes(const Problem& pb);
 // `mid`, if not null, is recorded between the partial kernel and the combine kernel
 hipError_t launch_shared(const Problem& pb, hipStream_t stream, hipEvent_t mid);
 
+// ---- causal prefill attention over each prompt (bf16, d = 128, Hq/Hkv <= 16)
+bool prefill_supported(int dtype, int Hq, int Hkv, int d);
+hipError_t launch_prefill(const void* q, const void* k, const void* v, const int32_t* lens, float* out, float* lse,
+                          int P, int Hq, int Hkv, int Lp_cap, float scale, hipStream_t stream);
+
 // ---- stand-alone log-sum-exp combine over [n_parts, n_rows, d] partials
 hipError_t launch_combine(const float* o_parts, const float* lse_parts, int n_parts, int64_t n_rows,
                           int d, float* out, float* lse, hipStream_t stream);

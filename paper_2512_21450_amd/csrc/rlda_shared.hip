@@ -744,6 +744,95 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   if (P.lse && c4 == 0) P.lse[row] = Z > 0.f ? M + __logf(Z) : -INFINITY;
 }
 
+// ---- prefill: causal attention of a prompt over itself, computed once per prompt (its K/V are the
+// shared prefix store of the decode steps).  One workgroup per (prompt, KV head, block of QB query
+// positions): the QB * r rows (position-major, then query head of the group) form up to four
+// 16-row blocks, one per wavefront, and share every K/V tile through LDS exactly as the G * r rows
+// of a decode group do in prefix_stream; a lane's row sees the keys below its own limit
+// (position + 1).  No key split: a workgroup walks all tiles up to its last position, so rows are
+// normalised and written directly.  Blocks are issued from the end of the prompt (most tiles) to
+// its start.
+struct PrefillParams {
+  const char* q; const char* k; const char* v; const int32_t* lens;
+  float* out; float* lse;
+  int P, Hq, Hkv, r, Lp_cap, QB, nqb;
+  float c;
+};
+
+__global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParams P) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int units = P.P * P.Hkv;
+  const int qb = P.nqb - 1 - (int)(blockIdx.x / units), pj = blockIdx.x % units;
+  const int p = pj / P.Hkv, j = pj % P.Hkv;
+  const int L = clampi(P.lens[p], 0, P.Lp_cap), a = qb * P.QB;
+  if (a >= L) return;                                       // the whole block is padding (same decision in every thread)
+  const int nq = min(P.QB, L - a), n_keys = a + nq, n_tiles = ceil_div(n_keys, TK);
+  // this lane's query row
+  const int row = 16 * wv + m16;
+  const bool ok = row < nq * P.r;
+  const int pos = a + (ok ? row / P.r : 0), h = j * P.r + (ok ? row % P.r : 0);
+  const int limit = pos + 1;                                // keys [0, limit) are visible; rows that do not exist see key 0 only
+  bf16x8 qf[1][4];
+  {
+    const char* qp = P.q + (((size_t)p * P.Lp_cap + pos) * P.Hq + h) * ROWB + 16 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const u32x4 v = ok ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+      qf[0][ks] = *reinterpret_cast<const bf16x8*>(&v);
+    }
+  }
+  const int wave_last = a + min(nq * P.r - 1, 16 * wv + 15) / P.r;   // last position any row of this wavefront holds (uniform)
+  const bool wave_has_rows = 16 * wv < nq * P.r;
+  const char* kb = P.k + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
+  const char* vb = P.v + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
+  const int lrow = lane >> 4, chunk = lane & 15;
+  u32x4 rk[8], rv[8];
+  auto issue = [&](int t) {                                 // tile t (if it exists) into this wavefront's registers
+    if (t < n_tiles) {
+      const int key0 = t * TK, last = min(TK, n_keys - key0) - 1;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const size_t off = (size_t)(key0 + min(4 * i + lrow, last)) * ROWB + 16 * chunk;
+        rk[i] = ldg16(kb + off);                            // the prompt's K/V are read by all its blocks: keep them cached
+        rv[i] = ldg16(vb + off);
+      }
+    }
+  };
+  WaveState<1> st;
+  init_state(st);
+  char* mine = lds + wv * STAGE_B;
+  issue(wv);
+  for (int g0 = 0; g0 < n_tiles; g0 += WG_WAVES) {
+    wait_vmem();
+    if (g0 + wv < n_tiles) stage_store<false>(mine, mine + TILE_B, rk, rv, lrow, chunk);
+    lds_barrier();
+    issue(g0 + WG_WAVES + wv);                              // next group in flight during the arithmetic
+#pragma unroll
+    for (int s2 = 0; s2 < WG_WAVES; ++s2) {
+      const int key0 = (g0 + s2) * TK;
+      if (g0 + s2 < n_tiles && wave_has_rows && key0 <= wave_last)       // tiles wholly in this wavefront's future are skipped
+        compute_tile<1>(lds + s2 * STAGE_B, lds + s2 * STAGE_B + TILE_B, limit - key0, qf, st, P.c, lane);
+    }
+    lds_barrier();                                          // stages are rewritten by the next group
+  }
+  // normalise and write the row
+  float l = st.l[0], lr = st.lr[0];
+  l += __shfl_xor(l, 16, 64);   l += __shfl_xor(l, 32, 64);
+  lr += __shfl_xor(lr, 16, 64); lr += __shfl_xor(lr, 32, 64);
+  if (ok) {
+    const float inv = 1.f / lr;
+    const size_t orow = ((size_t)p * P.Lp_cap + pos) * P.Hq + h;
+    float* o = P.out + orow * D + 4 * g;
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) {
+      const f32x4 v = st.O[0][ct] * inv;
+      *reinterpret_cast<float4*>(o + 16 * ct) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    if (P.lse && g == 0) P.lse[orow] = (st.m[0] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f;
+  }
+}
+
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout { size_t cum, pl, po, sl, so, total; };
@@ -841,6 +930,38 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   const int rows = P.B * P.Hq;
   if (ext) hipLaunchKernelGGL(combine_kernel<true>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
   else     hipLaunchKernelGGL(combine_kernel<false>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  return hipGetLastError();
+}
+
+bool prefill_supported(int dtype, int Hq, int Hkv, int d) {
+  return dtype == RLDA_BF16 && d == D && Hkv > 0 && Hq % Hkv == 0 && Hq / Hkv <= 16;
+}
+
+hipError_t launch_prefill(const void* q, const void* k, const void* v, const int32_t* lens, float* out, float* lse,
+                          int P_, int Hq, int Hkv, int Lp_cap, float scale, hipStream_t stream) {
+  PrefillParams P;
+  P.q = static_cast<const char*>(q); P.k = static_cast<const char*>(k); P.v = static_cast<const char*>(v);
+  P.lens = lens; P.out = out; P.lse = lse;
+  P.P = P_; P.Hq = Hq; P.Hkv = Hkv; P.r = Hq / Hkv; P.Lp_cap = Lp_cap;
+  P.QB = (16 * WG_WAVES) / P.r;                             // query positions per workgroup: up to 64 rows
+  P.nqb = ceil_div(Lp_cap, P.QB);
+  P.c = scale * 1.4426950408889634f;
+  {
+    static std::mutex mu;
+    static bool done[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64 || !done[dev]) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(prefill_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              LDS_BYTES);
+      if (e != hipSuccess) return e;
+      if (dev >= 0 && dev < 64) done[dev] = true;
+    }
+  }
+  const int64_t blocks = (int64_t)P.nqb * P_ * Hkv;
+  hipLaunchKernelGGL(prefill_kernel, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, stream, P);
   return hipGetLastError();
 }
 

@@ -280,3 +280,20 @@ def test_group_advantage_argument_checks():
     ds = B.make_group_advantage_desc(2, 4, 1, **ok); ds.struct_size = 8
     assert B.rl_group_advantage_raw(ds) == -4
     assert B._lib.rl_group_advantage(None, None) == -1
+
+
+# ---------------------------------------------------------------- rl_prefill_attn.h
+def test_prefill_descriptor_layout_and_errors():
+    assert ctypes.sizeof(B.rl_prefill_desc) == 32 + 6 * 8 and B.rl_prefill_desc.q.offset == 32
+    fake = 0x1000
+    ptrs = dict(q=fake, k=fake, v=fake, lens=fake, out=fake)
+    mk = lambda **kw: B.make_prefill_desc(**{**dict(dtype=B.RLDA_BF16, P=2, Hq=28, Hkv=4, d=128, Lp_cap=100, scale=0.1), **kw})
+    for kw, code in [(dict(dtype=B.RLDA_F32), -2), (dict(d=64), -2), (dict(Hq=64, Hkv=2), -2), (dict(Hq=7, Hkv=2), -2),
+                     (dict(P=-1), -1), (dict(Lp_cap=-1), -1), (dict(Hkv=0), -1)]:
+        assert B.rl_prefill_attn_raw(mk(**ptrs, **kw)) == code, kw
+    for missing in ptrs:
+        assert B.rl_prefill_attn_raw(mk(**{k: v for k, v in ptrs.items() if k != missing})) == -1, missing
+    assert B.rl_prefill_attn_raw(mk(P=0)) == 0 and B.rl_prefill_attn_raw(mk(Lp_cap=0)) == 0   # nothing to do
+    ds = mk(**ptrs); ds.struct_size = 4
+    assert B.rl_prefill_attn_raw(ds) == -4
+    assert B._lib.rl_prefill_attn(None, None) == -1
