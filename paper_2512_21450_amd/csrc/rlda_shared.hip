@@ -139,7 +139,8 @@ __device__ __forceinline__ void init_state(WaveState<NT>& st) {
 }
 
 // One 32-key tile (K at Kl, V at Vl in LDS, first `nvalid` keys real) against NT blocks of 16 query rows.
-template <int NT>
+// nvalid may differ from lane to lane (a causal limit); MASK = false: every key is real for every row.
+template <int NT, bool MASK = true>
 __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, int nvalid, const bf16x8 (&qf)[NT][4],
                                              WaveState<NT>& st, float c, int lane) {
   const int m16 = lane & 15, g = lane >> 4;
@@ -163,8 +164,8 @@ __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, int
     float sv[8];
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      sv[x] = (4 * g + x < nvalid) ? s0[nt][x] * c : -INFINITY;
-      sv[4 + x] = (16 + 4 * g + x < nvalid) ? s1[nt][x] * c : -INFINITY;
+      sv[x] = (!MASK || 4 * g + x < nvalid) ? s0[nt][x] * c : -INFINITY;
+      sv[4 + x] = (!MASK || 16 + 4 * g + x < nvalid) ? s1[nt][x] * c : -INFINITY;
     }
     float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
     tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
@@ -783,6 +784,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParam
     }
   }
   const int wave_last = a + min(nq * P.r - 1, 16 * wv + 15) / P.r;   // last position any row of this wavefront holds (uniform)
+  const int wave_first = a + (16 * wv) / P.r;               // first position; rows that do not exist see less, but are not stored
   const bool wave_has_rows = 16 * wv < nq * P.r;
   const char* kb = P.k + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
   const char* vb = P.v + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;
@@ -811,8 +813,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParam
 #pragma unroll
     for (int s2 = 0; s2 < WG_WAVES; ++s2) {
       const int key0 = (g0 + s2) * TK;
-      if (g0 + s2 < n_tiles && wave_has_rows && key0 <= wave_last)       // tiles wholly in this wavefront's future are skipped
-        compute_tile<1>(lds + s2 * STAGE_B, lds + s2 * STAGE_B + TILE_B, limit - key0, qf, st, P.c, lane);
+      if (g0 + s2 < n_tiles && wave_has_rows && key0 <= wave_last) {     // tiles wholly in this wavefront's future are skipped
+        if (key0 + TK <= wave_first + 1)                                 // wholly in every row's past: no masks
+          compute_tile<1, false>(lds + s2 * STAGE_B, lds + s2 * STAGE_B + TILE_B, TK, qf, st, P.c, lane);
+        else
+          compute_tile<1>(lds + s2 * STAGE_B, lds + s2 * STAGE_B + TILE_B, limit - key0, qf, st, P.c, lane);
+      }
     }
     lds_barrier();                                          // stages are rewritten by the next group
   }
