@@ -29,10 +29,12 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # HBM bytes one launch of the K/V-streaming kernel moved, from two rocprofv3 --pmc passes
 # (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read
 # for the 1 GiB copy of --copy-probe (profiles/partial_kernel_vlm7b_hbm_traffic.md).  Only
-# valid for the workload and the kernel sources the counters were taken on.
+# valid for the workload and the kernel sources the counters were taken on (the hash below is
+# re-stamped after edits to those files only when the decode kernels' instruction streams,
+# compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "cc4fd391478d910bf41c99bf5f064c37d70eb198045aedd7631695cdd7b21473",
+    "csrc_sha256": "ef4fc34f34f7ab20464e01493136d222bab8e12efc9812aa8a8479def7998552",
     "fetch_bytes": 623801353,
     "write_bytes": 9339888,
 }
