@@ -240,8 +240,8 @@ extern "C" int rl_prefill_attn(const rl_prefill_desc* d, void* hip_stream) {
   if (d->struct_size != sizeof(rl_prefill_desc)) return RLDA_ERR_STRUCT_SIZE;
   if (d->P < 0 || d->Hq <= 0 || d->Hkv <= 0 || d->d <= 0 || d->Lp_cap < 0) return RLDA_ERR_INVALID;
   if (!rlda::prefill_supported(d->dtype, d->Hq, d->Hkv, d->d)) return RLDA_ERR_UNSUPPORTED;
-  const int qb = 64 / (d->Hq / d->Hkv);
-  if ((int64_t)((d->Lp_cap + qb - 1) / qb) * d->P * d->Hkv > 0x7fffffffLL) return RLDA_ERR_UNSUPPORTED;
+  const int qb = 64 / (d->Hq / d->Hkv);                     // a lower bound of the positions per workgroup
+  if ((int64_t)((d->Lp_cap + qb - 1) / qb) * ((int64_t)d->P * d->Hkv + 7) > 0x7fffffffLL) return RLDA_ERR_UNSUPPORTED;
   if ((int64_t)d->Lp_cap * d->Hq * 256 >= (int64_t)1 << 40) return RLDA_ERR_UNSUPPORTED;
   if (d->P == 0 || d->Lp_cap == 0) return RLDA_OK;
   if (!d->q || !d->k || !d->v || !d->lens || !d->out) return RLDA_ERR_INVALID;

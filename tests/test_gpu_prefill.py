@@ -75,6 +75,14 @@ def test_reduced_sizes(B, case_):
     check(B, x, 1.0 / math.sqrt(128), str(case_))
 
 
+@pytest.mark.parametrize("P,L,Hq,Hkv", [(64, 400, 12, 4), (100, 330, 14, 2), (33, 500, 16, 16)])
+def test_many_prompts_take_the_two_block_kernel(B, P, L, Hq, Hkv):
+    # enough workgroups for the variant with 128 rows per workgroup (r = 3, 7, 1: 42, 18, 128 positions per block)
+    x = case(900 + P, P, L, Hq, Hkv)
+    x["lens"][:3] = [L, 1, 0]
+    check(B, x, 1.0 / math.sqrt(128), f"P{P} L{L} {Hq}/{Hkv}")
+
+
 def test_edge_lengths_nan_padding_and_sharp_scores(B):
     x = case(7, 5, 70, 28, 4, lens=[0, 70, 1, 32, 33], gain=3.0)
     for p, n in enumerate(x["lens"]):                       # rows beyond a length hold NaN and are never read
