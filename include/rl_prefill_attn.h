@@ -20,7 +20,7 @@
  * read.  bf16 inputs, fp32 accumulation on the matrix cores, softmax weights rounded
  * to bf16 before the value contraction (the arithmetic of the decode path), fp32
  * outputs.  Unlike the decode step this pass is bound by the matrix cores, not by
- * HBM: every K/V tile is used by up to 64 query rows.
+ * HBM: every K/V tile is used by up to 128 query rows.
  */
 #ifndef RL_PREFILL_ATTN_H
 #define RL_PREFILL_ATTN_H
