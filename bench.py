@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "8b86b7f58eef9ba66b0b695ce159c0ec7534e93cb367d793397f14a2168846fb",
+    "csrc_sha256": "0671409ffb26de578d5f7905840f2f6774ff1caff1b9f3e294df2d71f84a35bf",
     "fetch_bytes": 623801353,
     "write_bytes": 9339888,
 }

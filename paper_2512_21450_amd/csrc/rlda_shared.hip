@@ -11,7 +11,8 @@
 //                   transition s' = (s, a)) are streamed by single wavefronts.  Every maximal
 //                   run of tiles of one (prompt or sequence, KV head) yields a partial (o, lse).
 //   combine_kernel  merges the partials of every (sequence, head) by log-sum-exp and writes
-//                   out / lse.
+//                   out / lse (combine16_kernel: the same with half the lanes per row, for
+//                   batches of many units).
 //
 // Tile math (one wavefront, 16 query rows, 32 keys): scores are produced
 // transposed, S^T = K_tile * Q^T, with v_mfma_f32_16x16x32_bf16 (A = 16 keys x 32
@@ -755,6 +756,106 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   if (P.lse && c4 == 0) P.lse[row] = Z > 0.f ? M + __logf(Z) : -INFINITY;
 }
 
+// from this many prefix units (prompts x KV heads x row parts) on, rows have few enough parts for combine16_kernel
+constexpr int COMBINE16_MIN_UNITS = 128;
+
+// ---- the same with 16 lanes per row and 16 rows per workgroup, for batches of many units, whose rows
+// have few parts (a prefix unit is cut into about 1 + N_WG / units parts): half the wavefronts, so that
+// 2048 x 16 rows are one resident generation of workgroups instead of two, at the price of a shallower
+// first request (four parts instead of eight), which rows of many parts would pay in round trips.  Lane k of the row first owns part k:
+// all lse values of the row and the first four parts' values are requested in one round trip; the lse
+// values become weights with two 16-lane reductions; then every lane accumulates its 8 columns, one
+// 16-byte chunk of every stored partial row.  Parts are taken in line order, so the sum has one fixed order.
+template <bool EXT>
+__global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P) {
+  const int row = blockIdx.x * 16 + (threadIdx.x >> 4);
+  const int sub = threadIdx.x & 15;
+  const int coff = 16 * sub;                                // chunk `sub` of a stored partial row holds columns
+  const int ca = 32 * (sub >> 2) + 4 * (sub & 3), cb = ca + 16;   // ca .. ca+3 and cb .. cb+3 (see part_col_off)
+  if (row >= P.B * P.Hq) return;
+  const int b = row / P.Hq, h = row % P.Hq;
+  float* orow = P.out + (size_t)row * D;
+  if (EXT && P.active && P.active[b] == 0) {               // finished sequence: its prefix rows were computed, not used
+    *reinterpret_cast<float4*>(orow + ca) = make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(orow + cb) = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (P.lse && sub == 0) P.lse[row] = -INFINITY;
+    return;
+  }
+  const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
+  const int* X = P.cum;
+  const int cumP = X[P.P];
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
+  const int half = P.NH > 1 ? grow >> 6 : 0;
+  const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
+
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float M = -INFINITY, Z = 0.f;                             // running max and sum over batches of 16 parts
+  auto part_values = [&](int id) {
+    return *reinterpret_cast<const f16x8*>(reinterpret_cast<const char*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D) + coff);
+  };
+  for (int base = 0;; base += 16) {
+    // part `base + sub` of this row, as 2 * (row index in its partial array) + [suffix]
+    int n = 0, mine = -1;
+    for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
+      if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
+      ++n;
+    });
+    for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
+      if (n == base + sub) mine = 2 * ((b * P.Hkv + j + WG_WAVES * rank + v) * P.r + hi_) + 1;
+      ++n;
+    });
+    const int cnt = min(n - base, 16);
+    if (cnt <= 0) break;
+    // the first 4 parts' values are requested together with the lse values (one round trip)
+    f16x8 v4[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v4[u] = part_values(__shfl(mine, min(u, cnt - 1), 16));
+    const float2 ls = mine < 0 ? make_float2(-INFINITY, 0.f)
+                               : *reinterpret_cast<const float2*>((mine & 1 ? P.sl : P.pl) + 2 * (size_t)(mine >> 1));
+    const float l = ls.x;
+    float m = l;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 16));
+    const float Mn = fmaxf(M, m);                           // finite: every part holds at least one key
+    const float resc = __expf(M - Mn);
+    const float wgt = __expf(l - Mn);                       // lanes without a part: 0
+    const float wsc = wgt * ls.y;                           // weight times the stored row's scale
+    float zs = wgt;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) zs += __shfl_xor(zs, o, 16);
+    Z = Z * resc + zs;
+    M = Mn;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) acc[x] *= resc;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float wk = u < cnt ? __shfl(wsc, min(u, cnt - 1), 16) : 0.f;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) acc[x] = fmaf(wk, (float)v4[u][x], acc[x]);
+    }
+    for (int k0 = 4; k0 < cnt; k0 += 4) {
+      f16x8 v[4];
+      float wk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int k = min(k0 + u, cnt - 1);
+        wk[u] = k0 + u < cnt ? __shfl(wsc, k, 16) : 0.f;
+        v[u] = part_values(__shfl(mine, k, 16));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int x = 0; x < 8; ++x) acc[x] = fmaf(wk[u], (float)v[u][x], acc[x]);
+    }
+    if (n - base <= 16) break;
+  }
+  const float inv = Z > 0.f ? 1.f / Z : 0.f;
+  *reinterpret_cast<float4*>(orow + ca) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+  *reinterpret_cast<float4*>(orow + cb) = make_float4(acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv);
+  if (P.lse && sub == 0) P.lse[row] = Z > 0.f ? M + __logf(Z) : -INFINITY;
+}
+
 // ---- prefill: causal attention of a prompt over itself, computed once per prompt (its K/V are the
 // shared prefix store of the decode steps).  One workgroup per (prompt, KV head, block of QB query
 // positions): the QB * r rows (position-major, then query head of the group) form up to four
@@ -974,8 +1075,13 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
   }
   const int rows = P.B * P.Hq;
-  if (ext) hipLaunchKernelGGL(combine_kernel<true>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
-  else     hipLaunchKernelGGL(combine_kernel<false>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  if ((int64_t)ds.P * P.HkvP >= COMBINE16_MIN_UNITS) {
+    if (ext) hipLaunchKernelGGL(combine16_kernel<true>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
+    else     hipLaunchKernelGGL(combine16_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
+  } else {
+    if (ext) hipLaunchKernelGGL(combine_kernel<true>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+    else     hipLaunchKernelGGL(combine_kernel<false>, dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  }
   return hipGetLastError();
 }
 

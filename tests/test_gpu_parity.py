@@ -357,3 +357,26 @@ def test_many_short_sequences_fill_the_length_scan(B, P, plan):
                              t["suffix_lens"], 0.1, G, out, None)
     assert B.rl_decode_attn_plan(ds) == {"shared": B.RLDA_ALGO_SHARED, "simple": B.RLDA_ALGO_SIMPLE}[plan]
     check(x, 0.1, G, "bf16", "auto", f"P={P}", B)
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_rows_with_many_parts_in_the_16_lane_combine(B, paged):
+    """128 prefix units select the 16-lane combine kernel; one prompt and one sequence hold nearly all
+    keys, so their rows are cut among most workgroups: more parts per row than one request (4) and than
+    one batch of lanes (16) hold, next to rows with a single part and rows with none."""
+    import torch
+    P, G, Hq, Hkv, d = 64, 2, 4, 2, 128
+    pl = np.full(P, 8, np.int32)
+    pl[0], pl[9], pl[63] = 6000, 0, 700
+    sl = np.full(P * G, 5, np.int32)
+    sl[1], sl[18], sl[19], sl[127] = 4000, 0, 0, 900
+    x = util.random_case(77, P, G, Hq, Hkv, d, 6016, 4000, "bf16", plens=pl, slens=sl)
+    if not paged:
+        check(x, 0.1, G, "bf16", "auto", "many parts", B)
+        return
+    y = wl.to_pages(x, 64, seed=3)
+    t = util.to_device(y)
+    out, lse = util.gpu_run_paged(t, 0.1, G)
+    torch.cuda.synchronize()
+    ro, rl = util.oracle_paged(y, 0.1, G)
+    util.compare(out, lse, ro, rl, "bf16", "many parts, paged")
