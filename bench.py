@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "0671409ffb26de578d5f7905840f2f6774ff1caff1b9f3e294df2d71f84a35bf",
+    "csrc_sha256": "4235d3ff36b5640ce7031745c46e368a9b3665f8762956b7e782fe1dc7fdce32",
     "fetch_bytes": 623801353,
     "write_bytes": 9339888,
 }

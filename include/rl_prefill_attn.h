@@ -52,7 +52,7 @@ typedef struct {
  * Enqueue on `hip_stream` (hipStream_t as void*; NULL = default stream).  Asynchronous, allocates
  * nothing, needs no workspace.  Returns 0 or a negative code with the meaning of the RLDA_ERR_*
  * values of rl_decode_attn.h: -1 invalid argument (NULL tensor with work to do, negative size),
- * -2 unsupported (dtype, d, head ratio, more than 2^31 - 1 workgroups), -4 struct_size, -5 HIP
+ * -2 unsupported (dtype, d, head ratio, more than 2^31 - 1 workgroups, Lp_cap >= 2^24), -4 struct_size, -5 HIP
  * error.  Results are bit-reproducible from call to call.
  */
 int rl_prefill_attn(const rl_prefill_desc* desc, void* hip_stream);

@@ -243,6 +243,7 @@ extern "C" int rl_prefill_attn(const rl_prefill_desc* d, void* hip_stream) {
   const int qb = 64 / (d->Hq / d->Hkv);                     // a lower bound of the positions per workgroup
   if ((int64_t)((d->Lp_cap + qb - 1) / qb) * ((int64_t)d->P * d->Hkv + 7) > 0x7fffffffLL) return RLDA_ERR_UNSUPPORTED;
   if ((int64_t)d->Lp_cap * d->Hq * 256 >= (int64_t)1 << 40) return RLDA_ERR_UNSUPPORTED;
+  if (d->Lp_cap >= 1 << 24) return RLDA_ERR_UNSUPPORTED;    // byte offsets inside one (prompt, KV head) store are 32-bit
   if (d->P == 0 || d->Lp_cap == 0) return RLDA_OK;
   if (!d->q || !d->k || !d->v || !d->lens || !d->out) return RLDA_ERR_INVALID;
   const hipError_t e = rlda::launch_prefill(d->q, d->k, d->v, d->lens, d->out, d->lse, d->P, d->Hq, d->Hkv, d->Lp_cap,

@@ -27,6 +27,7 @@
 #include "rlda_sched.h"
 
 #include <mutex>
+#include <type_traits>
 
 namespace rlda {
 namespace {
@@ -980,6 +981,261 @@ __global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParam
   }
 }
 
+// ---- prefill, 128 rows per workgroup, K/V tiles moved from the store straight into LDS.
+//
+// What bounds prefill_kernel is not one unit but the order of a wavefront's own work: LDS read
+// latency, matrix products and vector ALU follow each other, and at 256 registers two wavefronts per
+// SIMD is all there is to overlap them.  The 64 registers that stage a K/V tile are what stands in
+// the way of issuing the LDS reads of the next phase a phase ahead, so here the tiles take the
+// direct path: global_load_lds_dwordx4 writes a lane's 16 bytes to LDS at (uniform base) + 16 * lane,
+// and the layout's xor pattern, being a permutation of the 16 chunks of a row, goes into the lane's
+// global address instead.  The compiler cannot tell which LDS bytes such a load writes and would make
+// every later LDS read wait for all of them; the fragment reads are therefore issued as asm, with
+// explicit waits that carry the destination registers as operands so that no use is moved above them.
+//
+// Schedule of a wavefront (tile t in stage t % 4; rounds of two tiles; buffer = round % 2):
+//     row maxima (t) | V(t) reads issued | weights and sums (t) | wait V(t) | [end of round: loads landed, barrier, issue the
+//     loads of round + 2 into the buffer just finished] | K(t+1) reads issued | value products (t) |
+//     wait K(t+1) | score products (t+1)
+// so that LDS latency lies under the vector ALU (V) and the matrix unit (K), and the matrix work of
+// one tile's second product and the next tile's first product is one uninterrupted run for the other
+// wavefront of the SIMD to put its softmax under.  Wavefront w moves the K (even w) or V (odd w) half
+// of tile w / 2 of a round.
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_rd128_asm(uint32_t addr) {
+  bf16x8 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_rd_tr16_asm(uint32_t addr) {
+  s16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+__device__ __forceinline__ void wait_k_frags(bf16x8 (&k)[4][2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(k[0][0]), "+v"(k[0][1]), "+v"(k[1][0]), "+v"(k[1][1]), "+v"(k[2][0]), "+v"(k[2][1]), "+v"(k[3][0]), "+v"(k[3][1]));
+}
+__device__ __forceinline__ void wait_v_frags(s16x4 (&v)[8][2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(v[0][0]), "+v"(v[0][1]), "+v"(v[1][0]), "+v"(v[1][1]), "+v"(v[2][0]), "+v"(v[2][1]), "+v"(v[3][0]), "+v"(v[3][1]),
+                 "+v"(v[4][0]), "+v"(v[4][1]), "+v"(v[5][0]), "+v"(v[5][1]), "+v"(v[6][0]), "+v"(v[6][1]), "+v"(v[7][0]), "+v"(v[7][1]));
+}
+template <int STAGE>
+__device__ __forceinline__ void read_k_frags(const uint32_t (&ka)[4], bf16x8 (&k)[4][2]) {
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) {
+    k[ks][0] = lds_rd128_asm<STAGE * STAGE_B>(ka[ks]);
+    k[ks][1] = lds_rd128_asm<STAGE * STAGE_B + 16 * ROWB>(ka[ks]);
+  }
+}
+template <int STAGE>
+__device__ __forceinline__ void read_v_frags(const uint32_t (&va)[8], s16x4 (&v)[8][2]) {
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) {
+    v[ct][0] = lds_rd_tr16_asm<STAGE * STAGE_B + TILE_B>(va[ct]);
+    v[ct][1] = lds_rd_tr16_asm<STAGE * STAGE_B + TILE_B + 16 * ROWB>(va[ct]);
+  }
+}
+template <int NT>
+__device__ __forceinline__ void score_products(const bf16x8 (&k)[4][2], const bf16x8 (&qf)[NT][4], f32x4 (&s0)[NT], f32x4 (&s1)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) { s0[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[nt] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+      s0[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[ks][0], qf[nt][ks], s0[nt], 0, 0, 0);
+      s1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[ks][1], qf[nt][ks], s1[nt], 0, 0, 0);
+    }
+}
+// the softmax step of compute_tile on scores already in registers, in two halves: the scaled, masked
+// scores and the row maxima (whose cross-lane reads share the LDS queue: the V reads are issued after
+// them), then the weights, row sums and the rescaling
+template <int NT, bool MASK>
+__device__ __forceinline__ void softmax_max(const f32x4 (&s0)[NT], const f32x4 (&s1)[NT], const int (&nvalid)[NT],
+                                            const WaveState<NT>& st, float c, int g, float (&sv)[NT][8], float (&m_new)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      sv[nt][x] = (!MASK || 4 * g + x < nvalid[nt]) ? s0[nt][x] * c : -INFINITY;
+      sv[nt][4 + x] = (!MASK || 16 + 4 * g + x < nvalid[nt]) ? s1[nt][x] * c : -INFINITY;
+    }
+    float tmax = fmaxf(fmaxf(fmaxf(sv[nt][0], sv[nt][1]), fmaxf(sv[nt][2], sv[nt][3])),
+                       fmaxf(fmaxf(sv[nt][4], sv[nt][5]), fmaxf(sv[nt][6], sv[nt][7])));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+    m_new[nt] = fmaxf(st.m[nt], tmax);                       // finite from the first tile on: key 0 is visible to every row
+  }
+}
+template <int NT>
+__device__ __forceinline__ void softmax_weights(const float (&sv)[NT][8], const float (&m_new)[NT], WaveState<NT>& st, bf16x8 (&pb)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new[nt]);
+    float se = 0.f, sr = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const float pe = __builtin_amdgcn_exp2f(sv[nt][x] - m_new[nt]);
+      const __bf16 pr = static_cast<__bf16>(pe);
+      pb[nt][x] = pr;
+      se += pe;
+      sr += static_cast<float>(pr);
+    }
+    st.l[nt] = st.l[nt] * alpha + se;
+    st.lr[nt] = st.lr[nt] * alpha + sr;
+    st.m[nt] = m_new[nt];
+    if (__any(alpha != 1.f)) {
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
+    }
+  }
+}
+template <int NT>
+__device__ __forceinline__ void value_products(const s16x4 (&v)[8][2], const bf16x8 (&pb)[NT], WaveState<NT>& st) {
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) {
+    union { s16x4 h[2]; bf16x8 v; } vt;
+    vt.h[0] = v[ct][0]; vt.h[1] = v[ct][1];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+      st.O[nt][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.v, pb[nt], st.O[nt][ct], 0, 0, 0);
+  }
+}
+#define RLDA_G2L(src, dst, off)                                                                                 \
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),                        \
+                                   (__attribute__((address_space(3))) void*)(dst), 16, (off), 0)
+
+template <int NTP>
+__global__ void __launch_bounds__(NTHREADS, 2) prefill2_kernel(const PrefillParams P) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  constexpr int N_XCD = 8, WROWS = 16 * NTP;
+  const int units = P.P * P.Hkv;
+  const int xcd = blockIdx.x % N_XCD, seq = blockIdx.x / N_XCD;
+  const int pj = (seq / P.nqb) * N_XCD + xcd, qb = P.nqb - 1 - seq % P.nqb;
+  if (pj >= units) return;
+  const int p = pj / P.Hkv, j = pj % P.Hkv;
+  const int L = clampi(P.lens[p], 0, P.Lp_cap), a = qb * P.QB;
+  if (a >= L) return;
+  const int nq = min(P.QB, L - a), n_keys = a + nq, n_tiles = ceil_div(n_keys, TK), nrows = nq * P.r;
+  bool ok[NTP];
+  int pos[NTP], h[NTP], limit[NTP];
+  bf16x8 qf[NTP][4];
+#pragma unroll
+  for (int nt = 0; nt < NTP; ++nt) {
+    const int row = WROWS * wv + 16 * nt + m16;
+    ok[nt] = row < nrows;
+    pos[nt] = a + (ok[nt] ? row / P.r : 0);
+    h[nt] = j * P.r + (ok[nt] ? row % P.r : 0);
+    limit[nt] = pos[nt] + 1;
+    const char* qp = P.q + (((size_t)p * P.Lp_cap + pos[nt]) * P.Hq + h[nt]) * ROWB + 16 * g;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const u32x4 v = ok[nt] ? ldg16(qp + 64 * ks) : u32x4{0, 0, 0, 0};
+      qf[nt][ks] = *reinterpret_cast<const bf16x8*>(&v);
+    }
+  }
+  const int wave_first = a + (WROWS * wv) / P.r;            // first position any row of this wavefront holds
+  const bool wave_has_rows = WROWS * wv < nrows;
+  // LDS addresses of this lane's fragment reads inside stage 0 (the stage goes into the immediate offset)
+  const uint32_t l0 = (uint32_t)(uintptr_t)RLDA_LDS(char, lds);
+  uint32_t ka[4], va[8];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) ka[ks] = l0 + k_off(m16, 4 * ks + g);
+  const int vrow = 4 * g + (m16 >> 2);
+#pragma unroll
+  for (int ct = 0; ct < 8; ++ct) va[ct] = l0 + v_off(vrow, 2 * ct + ((m16 & 3) >> 1)) + ((m16 & 1) << 3);
+  // this wavefront's share of a round's loads: eight instructions of four rows.  Instruction i puts tile row
+  // 4 i + lane / 16 into LDS; the store's row is clamped to the last real key (a partial last tile re-reads it;
+  // those keys are masked), and the 16-byte chunk a lane fetches is its LDS chunk xor the row's pattern.
+  const int kind = uni(wv & 1), sub = uni(wv >> 1), lrow = lane >> 4, chunk = lane & 15;
+  const char* gb = (kind ? P.v : P.k) + (size_t)(p * P.Hkv + j) * P.Lp_cap * ROWB;      // uniform
+  const int cx = kind ? chunk ^ (lrow << 1) : chunk ^ lrow;                              // V: (row & 7) << 1, K: row & 15
+  auto issue = [&](int round) {
+    const int t = 2 * round + sub;
+    if (t >= n_tiles) return;
+    const int key0 = t * TK;
+    char* dst = lds + uni((2 * (round & 1) + sub) * STAGE_B + kind * TILE_B);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int ci = kind ? ((4 * i) & 4) << 1 : (4 * i) & 12;
+      const uint32_t off = (uint32_t)min(key0 + 4 * i + lrow, n_keys - 1) * ROWB + ((cx ^ ci) << 4);
+      RLDA_G2L(gb + off, dst + i * 1024, 0);
+    }
+  };
+  WaveState<NTP> st;
+  init_state(st);
+  f32x4 s0[NTP], s1[NTP];
+  bf16x8 pb[NTP], kf[4][2];
+  s16x4 vf[8][2];
+  issue(0);
+  issue(1);
+  wait_vmem();
+  __builtin_amdgcn_s_barrier();
+  if (wave_has_rows) {
+    read_k_frags<0>(ka, kf);
+    wait_k_frags(kf);
+    score_products<NTP>(kf, qf, s0, s1);
+  }
+  // one tile; STAGE = t % 4 is a compile-time constant of the unrolled body
+  auto tile = [&](auto stage_c, int t) {
+    constexpr int STAGE = decltype(stage_c)::value;
+    const int key0 = t * TK;
+    if (wave_has_rows) {
+      float sv[NTP][8], m_new[NTP];
+      int nv[NTP];
+#pragma unroll
+      for (int nt = 0; nt < NTP; ++nt) nv[nt] = limit[nt] - key0;
+      if (key0 + TK <= wave_first + 1) softmax_max<NTP, false>(s0, s1, nv, st, P.c, g, sv, m_new);   // wholly in every row's past
+      else                             softmax_max<NTP, true>(s0, s1, nv, st, P.c, g, sv, m_new);
+      asm volatile("" : "+v"(m_new[0]), "+v"(m_new[NTP - 1]));   // the cross-lane reads have returned before the V reads queue up behind them
+      read_v_frags<STAGE>(va, vf);
+      softmax_weights<NTP>(sv, m_new, st, pb);
+      wait_v_frags(vf);
+    }
+    if ((STAGE & 1) || t == n_tiles - 1) {                  // the round's last tile: every fragment of the round is in registers
+      wait_vmem();                                          // this wavefront's loads of the next round have landed
+      __builtin_amdgcn_s_barrier();
+      issue((t >> 1) + 2);                                  // into the buffer the round just left
+    }
+    if (wave_has_rows) {
+      if (t + 1 < n_tiles) read_k_frags<(STAGE + 1) & 3>(ka, kf);
+      value_products<NTP>(vf, pb, st);
+      if (t + 1 < n_tiles) {
+        wait_k_frags(kf);
+        score_products<NTP>(kf, qf, s0, s1);
+      }
+    }
+  };
+  for (int t0 = 0; t0 < n_tiles; t0 += 4) {
+    tile(std::integral_constant<int, 0>{}, t0);
+    if (t0 + 1 < n_tiles) tile(std::integral_constant<int, 1>{}, t0 + 1);
+    if (t0 + 2 < n_tiles) tile(std::integral_constant<int, 2>{}, t0 + 2);
+    if (t0 + 3 < n_tiles) tile(std::integral_constant<int, 3>{}, t0 + 3);
+  }
+  // normalise and write the rows
+#pragma unroll
+  for (int nt = 0; nt < NTP; ++nt) {
+    float l = st.l[nt], lr = st.lr[nt];
+    l += __shfl_xor(l, 16, 64);   l += __shfl_xor(l, 32, 64);
+    lr += __shfl_xor(lr, 16, 64); lr += __shfl_xor(lr, 32, 64);
+    if (ok[nt]) {
+      const float inv = 1.f / lr;
+      const size_t orow = ((size_t)p * P.Lp_cap + pos[nt]) * P.Hq + h[nt];
+      float* o = P.out + orow * D + 4 * g;
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+        const f32x4 v = st.O[nt][ct] * inv;
+        *reinterpret_cast<float4*>(o + 16 * ct) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+      if (P.lse && g == 0) P.lse[orow] = (st.m[nt] + __builtin_amdgcn_logf(l)) * 0.69314718055994531f;
+    }
+  }
+}
+
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 struct Layout { size_t cum, pl, po, sl, so, total; };
@@ -1097,15 +1353,16 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, const int
   P.P = P_; P.Hq = Hq; P.Hkv = Hkv; P.r = Hq / Hkv; P.Lp_cap = Lp_cap;
   P.c = scale * 1.4426950408889634f;
   // Two 16-row blocks per wavefront (128 rows per workgroup) amortise every LDS read, barrier and
-  // staged tile over twice the matrix work (measured: 440 -> 514 Tflop/s on 32 prompts of 1280 tokens);
-  // small problems keep one block so that there are enough workgroups for 256 compute units.
+  // tile over twice the matrix work (measured with the register-staged kernel: 440 -> 514 Tflop/s on
+  // 32 prompts of 1280 tokens; prefill2_kernel, which they run on: 592); small problems keep one
+  // block, and the register-staged kernel, so that there are enough workgroups for 256 compute units.
   const int rows1 = 16 * WG_WAVES;
   const int64_t units8 = (int64_t)8 * ceil_div(P_ * Hkv, 8);              // eight XCDs, whole rounds of units
   const bool two = units8 * ceil_div(Lp_cap, (2 * rows1) / P.r) >= 4 * N_WG;
   P.QB = ((two ? 2 : 1) * rows1) / P.r;                     // query positions per workgroup
   P.nqb = ceil_div(Lp_cap, P.QB);
   typedef void (*kern_t)(const PrefillParams);
-  const kern_t kern = two ? prefill_kernel<2> : prefill_kernel<1>;
+  const kern_t kern = two ? prefill2_kernel<2> : prefill_kernel<1>;
   {
     static std::mutex mu;
     static bool done[64] = {};
@@ -1114,7 +1371,7 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, const int
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (const kern_t kf : {static_cast<kern_t>(prefill_kernel<1>), static_cast<kern_t>(prefill_kernel<2>)}) {
+      for (const kern_t kf : {static_cast<kern_t>(prefill_kernel<1>), static_cast<kern_t>(prefill2_kernel<2>)}) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kf), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }
