@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "4235d3ff36b5640ce7031745c46e368a9b3665f8762956b7e782fe1dc7fdce32",
+    "csrc_sha256": "87c9493db7cf9087ec88556b8403b3a2af9ffe946201bc0aff6a250ef1093fb6",
     "fetch_bytes": 623801353,
     "write_bytes": 9339888,
 }

@@ -1050,9 +1050,29 @@ __device__ __forceinline__ void score_products(const bf16x8 (&k)[4][2], const bf
       s1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[ks][1], qf[nt][ks], s1[nt], 0, 0, 0);
     }
 }
-// the softmax step of compute_tile on scores already in registers, in two halves: the scaled, masked
-// scores and the row maxima (whose cross-lane reads share the LDS queue: the V reads are issued after
-// them), then the weights, row sums and the rescaling
+// The softmax step on scores already in registers, in two halves (the V reads are issued between
+// them): the masked scores and the row maxima, then the weights, row sums and the rescaling.  Same
+// quotient sum(p v) / sum(p) as compute_tile, with less vector-ALU work per score, which this
+// kernel (unlike the memory-bound decode kernels) feels:
+//   * the score factor c goes into the exponent's fma instead of a multiply of its own;
+//   * maxima are taken as the median of (a, b, +inf): fmaxf has to return the other operand for a
+//     signalling NaN, for which the compiler first passes every operand it cannot prove quiet (a
+//     matrix-unit result, a cross-lane read) through an instruction of its own (the +inf comes
+//     through an empty asm so that the median is not folded back into fmaxf; no score is NaN here:
+//     keys past a row's limit are replaced by -inf before, and stores hold numbers);
+//   * the two cross-lane steps of a row maximum are gfx950's lane-swap instructions (rows of 16
+//     lanes, then halves of 32) instead of reads through the LDS queue;
+//   * a row's reference maximum moves only when a tile's maximum exceeds it by more than
+//     RESCALE_GAP powers of two (or on the row's first tile): until then the exponentials are taken
+//     against the stale maximum, are at most 2^RESCALE_GAP, and the 32 accumulator registers of a
+//     row block are left alone;
+//   * the sum of the bf16-rounded weights is a two-element dot product per register pair.
+constexpr float RESCALE_GAP = 8.f;
+__device__ __forceinline__ float max_raw(float a, float b) {
+  uint32_t inf = 0x7f800000u;
+  asm("" : "+s"(inf));
+  return __builtin_amdgcn_fmed3f(a, b, __uint_as_float(inf));
+}
 template <int NT, bool MASK>
 __device__ __forceinline__ void softmax_max(const f32x4 (&s0)[NT], const f32x4 (&s1)[NT], const int (&nvalid)[NT],
                                             const WaveState<NT>& st, float c, int g, float (&sv)[NT][8], float (&m_new)[NT]) {
@@ -1060,37 +1080,48 @@ __device__ __forceinline__ void softmax_max(const f32x4 (&s0)[NT], const f32x4 (
   for (int nt = 0; nt < NT; ++nt) {
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
-      sv[nt][x] = (!MASK || 4 * g + x < nvalid[nt]) ? s0[nt][x] * c : -INFINITY;
-      sv[nt][4 + x] = (!MASK || 16 + 4 * g + x < nvalid[nt]) ? s1[nt][x] * c : -INFINITY;
+      sv[nt][x] = (!MASK || 4 * g + x < nvalid[nt]) ? s0[nt][x] : -INFINITY;
+      sv[nt][4 + x] = (!MASK || 16 + 4 * g + x < nvalid[nt]) ? s1[nt][x] : -INFINITY;
     }
-    float tmax = fmaxf(fmaxf(fmaxf(sv[nt][0], sv[nt][1]), fmaxf(sv[nt][2], sv[nt][3])),
-                       fmaxf(fmaxf(sv[nt][4], sv[nt][5]), fmaxf(sv[nt][6], sv[nt][7])));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-    m_new[nt] = fmaxf(st.m[nt], tmax);                       // finite from the first tile on: key 0 is visible to every row
+    float tmax = max_raw(max_raw(max_raw(sv[nt][0], sv[nt][1]), max_raw(sv[nt][2], sv[nt][3])),
+                         max_raw(max_raw(sv[nt][4], sv[nt][5]), max_raw(sv[nt][6], sv[nt][7])));
+    {
+      // swap(x, x) returns (x with its odd rows replaced by the even ones, x with its even rows replaced by
+      // the odd ones), resp. the same for the two halves of 32 lanes: their maximum is max(x[l], x[l ^ 16 or 32])
+      typedef unsigned int u32p __attribute__((ext_vector_type(2)));
+      const u32p a = __builtin_amdgcn_permlane16_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+      tmax = max_raw(__uint_as_float(a[0]), __uint_as_float(a[1]));
+      const u32p b = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+      tmax = max_raw(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    }
+    m_new[nt] = max_raw(st.m[nt], tmax * c);
   }
 }
 template <int NT>
-__device__ __forceinline__ void softmax_weights(const float (&sv)[NT][8], const float (&m_new)[NT], WaveState<NT>& st, bf16x8 (&pb)[NT]) {
+__device__ __forceinline__ void softmax_weights(const float (&sv)[NT][8], const float (&m_new)[NT], WaveState<NT>& st, bf16x8 (&pb)[NT], float c) {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new[nt]);
-    float se = 0.f, sr = 0.f;
-#pragma unroll
-    for (int x = 0; x < 8; ++x) {
-      const float pe = __builtin_amdgcn_exp2f(sv[nt][x] - m_new[nt]);
-      const __bf16 pr = static_cast<__bf16>(pe);
-      pb[nt][x] = pr;
-      se += pe;
-      sr += static_cast<float>(pr);
-    }
-    st.l[nt] = st.l[nt] * alpha + se;
-    st.lr[nt] = st.lr[nt] * alpha + sr;
-    st.m[nt] = m_new[nt];
-    if (__any(alpha != 1.f)) {
+    if (__any(m_new[nt] > st.m[nt] + RESCALE_GAP)) {         // first tile: -inf + gap = -inf
+      const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new[nt]);
+      st.l[nt] *= alpha;
+      st.lr[nt] *= alpha;
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
+      st.m[nt] = m_new[nt];
     }
+    const float nm = -st.m[nt];
+    float se = 0.f, sr = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; x += 2) {
+      const float pe0 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x], c, nm));
+      const float pe1 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x + 1], c, nm));
+      const bf16x2 pr = __builtin_convertvector(f32x2{pe0, pe1}, bf16x2);
+      pb[nt][x] = pr[0]; pb[nt][x + 1] = pr[1];
+      se += pe0 + pe1;
+      sr = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)}, sr, false);
+    }
+    st.l[nt] += se;
+    st.lr[nt] += sr;
   }
 }
 template <int NT>
@@ -1191,9 +1222,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) prefill2_kernel(const PrefillPara
       for (int nt = 0; nt < NTP; ++nt) nv[nt] = limit[nt] - key0;
       if (key0 + TK <= wave_first + 1) softmax_max<NTP, false>(s0, s1, nv, st, P.c, g, sv, m_new);   // wholly in every row's past
       else                             softmax_max<NTP, true>(s0, s1, nv, st, P.c, g, sv, m_new);
-      asm volatile("" : "+v"(m_new[0]), "+v"(m_new[NTP - 1]));   // the cross-lane reads have returned before the V reads queue up behind them
       read_v_frags<STAGE>(va, vf);
-      softmax_weights<NTP>(sv, m_new, st, pb);
+      softmax_weights<NTP>(sv, m_new, st, pb, P.c);
       wait_v_frags(vf);
     }
     if ((STAGE & 1) || t == n_tiles - 1) {                  // the round's last tile: every fragment of the round is in registers
