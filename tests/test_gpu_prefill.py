@@ -83,6 +83,19 @@ def test_many_prompts_take_the_two_block_kernel(B, P, L, Hq, Hkv):
     check(B, x, 1.0 / math.sqrt(128), f"P{P} L{L} {Hq}/{Hkv}")
 
 
+@pytest.mark.parametrize("Hq,Hkv", [(4, 2), (14, 2)])
+def test_every_length_in_the_128_row_kernel(B, Hq, Hkv):
+    """Prompt lengths 0 .. 161 over 360 prompts (enough workgroups for the 128-row kernel at a capacity of 161):
+    every number of tiles from one to six, every size of a partial last tile, first and last rounds of one and
+    of two tiles, blocks whose last wavefronts hold no row, NaN beyond every length."""
+    L = 161
+    lens = np.arange(360) % (L + 1)
+    x = case(31 + Hq, 360, L, Hq, Hkv, lens=lens, gain=2.0)
+    for p, n in enumerate(lens):
+        x["k"][p, :, n:] = 0x7FC0; x["v"][p, :, n:] = 0x7FC0; x["q"][p, n:] = 0x7FC0
+    check(B, x, 0.11, f"all lengths {Hq}/{Hkv}")
+
+
 def test_edge_lengths_nan_padding_and_sharp_scores(B):
     x = case(7, 5, 70, 28, 4, lens=[0, 70, 1, 32, 33], gain=3.0)
     for p, n in enumerate(x["lens"]):                       # rows beyond a length hold NaN and are never read
