@@ -65,7 +65,7 @@ typedef enum { RLDA_F32 = 0, RLDA_BF16 = 1, RLDA_BF16_KV8 = 2 } rlda_dtype;
 
 /* Kernel selection. */
 typedef enum {
-  RLDA_ALGO_AUTO = 0,      /* shared-prefix MFMA path when the shape allows it, else SIMPLE */
+  RLDA_ALGO_AUTO = 0,      /* shared-prefix MFMA path when the shape allows it (and scale > 0), else SIMPLE */
   RLDA_ALGO_SIMPLE = 1,    /* one wavefront per (sequence, query head), no sharing, no split */
   RLDA_ALGO_SHARED = 2     /* force the shared-prefix path; RLDA_ERR_UNSUPPORTED if not possible */
 } rlda_algo;
@@ -93,7 +93,8 @@ typedef struct {
   int32_t  P, G;               /* prompts, samples per prompt; sequence b = p*G + g              */
   int32_t  Hq, Hkv, d;         /* query heads, KV heads (Hq % Hkv == 0), head dim (64 or 128)    */
   int32_t  Lp_cap, Ls_cap;     /* row capacity of the prefix / suffix KV buffers (>= 0)          */
-  float    scale;              /* multiplies <q,k> before the softmax                            */
+  float    scale;              /* multiplies <q,k> before the softmax; any finite value (the shared-prefix
+                                  path takes scale > 0 only, other values run on RLDA_ALGO_SIMPLE)    */
   const void*    q;            /* [B, Hq, d]                                                     */
   const void*    k_prefix;     /* [P, Hkv, Lp_cap, d]   (may be NULL if Lp_cap == 0)             */
   const void*    v_prefix;     /* [P, Hkv, Lp_cap, d]                                            */
@@ -105,7 +106,7 @@ typedef struct {
   float*   lse;                /* [B, Hq]    fp32, natural log; may be NULL                      */
   void*    workspace;          /* device scratch, 256-byte aligned, may be NULL if 0 bytes needed */
   size_t   workspace_bytes;
-  const float* k_scale;        /* [Hkv] fp32, RLDA_BF16_KV8 only (else ignored); NULL = all 1     */
+  const float* k_scale;        /* [Hkv] fp32 > 0, RLDA_BF16_KV8 only (else ignored); NULL = all 1 */
   const float* v_scale;        /* [Hkv] fp32, likewise                                           */
 } rlda_desc;
 
@@ -213,7 +214,7 @@ typedef struct {
   float*   lse;                /* [B, Hq] fp32; may be NULL                                      */
   void*    workspace;
   size_t   workspace_bytes;    /* >= rl_decode_attn_paged_workspace_bytes                        */
-  const float* k_scale;        /* [Hkv] fp32, RLDA_BF16_KV8 only; NULL = all 1                   */
+  const float* k_scale;        /* [Hkv] fp32 > 0, RLDA_BF16_KV8 only; NULL = all 1               */
   const float* v_scale;        /* [Hkv] fp32, likewise                                           */
 } rlda_paged_desc;
 

@@ -39,7 +39,7 @@ typedef struct {
   int32_t  P;                 /* prompts (>= 0)                                                  */
   int32_t  Hq, Hkv, d;        /* Hq % Hkv == 0, Hq/Hkv <= 16, d = 128                            */
   int32_t  Lp_cap;            /* row capacity of q / k / v / out per prompt (>= 0)               */
-  float    scale;
+  float    scale;              /* multiplies <q,k> before the softmax; any finite value           */
   const void*    q;           /* [P, Lp_cap, Hq, d]                                              */
   const void*    k;           /* [P, Hkv, Lp_cap, d]  the prefix store layout of rl_decode_attn  */
   const void*    v;           /* [P, Hkv, Lp_cap, d]                                             */

@@ -140,9 +140,86 @@ __device__ __forceinline__ void init_state(WaveState<NT>& st) {
   }
 }
 
+// The softmax step on scores already in registers, in two halves (prefill2_kernel issues its V reads
+// between them): the masked scores and the row maxima, then the weights, row sums and the rescaling.
+// The same quotient sum(p v) / sum(p) as the plain form inside compute_tile, with less vector-ALU work
+// per score.  The score factor c must be positive.
+//   * the score factor c goes into the exponent's fma instead of a multiply of its own;
+//   * maxima are taken as the median of (a, b, +inf): fmaxf has to return the other operand for a
+//     signalling NaN, for which the compiler first passes every operand it cannot prove quiet (a
+//     matrix-unit result, a cross-lane read) through an instruction of its own (the +inf comes
+//     through an empty asm so that the median is not folded back into fmaxf; no score is NaN here:
+//     keys past a row's limit are replaced by -inf before, and stores hold numbers);
+//   * the two cross-lane steps of a row maximum are gfx950's lane-swap instructions (rows of 16
+//     lanes, then halves of 32) instead of reads through the LDS queue;
+//   * a row's reference maximum moves only when a tile's maximum exceeds it by more than
+//     RESCALE_GAP powers of two (or on the row's first tile): until then the exponentials are taken
+//     against the stale maximum, are at most 2^RESCALE_GAP, and the 32 accumulator registers of a
+//     row block are left alone;
+//   * the sum of the bf16-rounded weights is a two-element dot product per register pair.
+constexpr float RESCALE_GAP = 8.f;
+__device__ __forceinline__ float max_raw(float a, float b) {
+  uint32_t inf = 0x7f800000u;
+  asm("" : "+s"(inf));
+  return __builtin_amdgcn_fmed3f(a, b, __uint_as_float(inf));
+}
+template <int NT, bool MASK>
+__device__ __forceinline__ void softmax_max(const f32x4 (&s0)[NT], const f32x4 (&s1)[NT], const int (&nvalid)[NT],
+                                            const WaveState<NT>& st, float c, int g, float (&sv)[NT][8], float (&m_new)[NT]) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      sv[nt][x] = (!MASK || 4 * g + x < nvalid[nt]) ? s0[nt][x] : -INFINITY;
+      sv[nt][4 + x] = (!MASK || 16 + 4 * g + x < nvalid[nt]) ? s1[nt][x] : -INFINITY;
+    }
+    float tmax = max_raw(max_raw(max_raw(sv[nt][0], sv[nt][1]), max_raw(sv[nt][2], sv[nt][3])),
+                         max_raw(max_raw(sv[nt][4], sv[nt][5]), max_raw(sv[nt][6], sv[nt][7])));
+    {
+      // swap(x, x) returns (x with its odd rows replaced by the even ones, x with its even rows replaced by
+      // the odd ones), resp. the same for the two halves of 32 lanes: their maximum is max(x[l], x[l ^ 16 or 32])
+      typedef unsigned int u32p __attribute__((ext_vector_type(2)));
+      const u32p a = __builtin_amdgcn_permlane16_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+      tmax = max_raw(__uint_as_float(a[0]), __uint_as_float(a[1]));
+      const u32p b = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
+      tmax = max_raw(__uint_as_float(b[0]), __uint_as_float(b[1]));
+    }
+    m_new[nt] = max_raw(st.m[nt], tmax * c);
+  }
+}
+template <int NT>
+__device__ __forceinline__ void softmax_weights(const float (&sv)[NT][8], const float (&m_new)[NT], WaveState<NT>& st, bf16x8 (&pb)[NT], float c) {
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    if (__any(m_new[nt] > st.m[nt] + RESCALE_GAP)) {         // first tile: -inf + gap = -inf
+      const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new[nt]);
+      st.l[nt] *= alpha;
+      st.lr[nt] *= alpha;
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
+      st.m[nt] = m_new[nt];
+    }
+    const float nm = -st.m[nt];
+    float se = 0.f, sr = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; x += 2) {
+      const float pe0 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x], c, nm));
+      const float pe1 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x + 1], c, nm));
+      const bf16x2 pr = __builtin_convertvector(f32x2{pe0, pe1}, bf16x2);
+      pb[nt][x] = pr[0]; pb[nt][x + 1] = pr[1];
+      se += pe0 + pe1;
+      sr = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)}, sr, false);
+    }
+    st.l[nt] += se;
+    st.lr[nt] += sr;
+  }
+}
 // One 32-key tile (K at Kl, V at Vl in LDS, first `nvalid` keys real) against NT blocks of 16 query rows.
 // nvalid may differ from lane to lane (a causal limit); MASK = false: every key is real for every row.
-template <int NT, bool MASK = true>
+// LEAN: the softmax step in the form above (needs c > 0: the launchers send other scales elsewhere); the
+// decode kernels use it (their e4m3 instantiations, which have the conversions on the vector ALU as well,
+// run 3-4 % faster for it, the bf16 ones the same), the register-staged prefill kernel the plain form.
+template <int NT, bool MASK = true, bool LEAN = false>
 __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, const int (&nvalid)[NT],
                                              const bf16x8 (&qf)[NT][4], WaveState<NT>& st, float c, int lane) {
   const int m16 = lane & 15, g = lane >> 4;
@@ -161,6 +238,11 @@ __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, con
     }
   }
   bf16x8 pb[NT];
+  if constexpr (LEAN) {
+    float sv[NT][8], m_new[NT];
+    softmax_max<NT, MASK>(s0, s1, nvalid, st, c, g, sv, m_new);
+    softmax_weights<NT>(sv, m_new, st, pb, c);
+  } else {
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
     float sv[8];
@@ -191,6 +273,7 @@ __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, con
       for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
     }
   }
+  }
   // lane (m16, g) of a 16-lane block addresses row 4g + m16/4, columns 16ct + 4(m16%4)..+3 and
   // receives V[4g..4g+3][16ct + m16]: the A operand of O^T += V^T P^T for the keys its P holds.
   const int vrow = 4 * g + (m16 >> 2);
@@ -208,13 +291,13 @@ __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, con
 }
 
 // the same with one key count for all row blocks (the decode kernels: a tile's tail)
-template <int NT, bool MASK = true>
+template <int NT, bool MASK = true, bool LEAN = false>
 __device__ __forceinline__ void compute_tile(const char* Kl, const char* Vl, int nvalid, const bf16x8 (&qf)[NT][4],
                                              WaveState<NT>& st, float c, int lane) {
   int nv[NT];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) nv[nt] = nvalid;
-  compute_tile<NT, MASK>(Kl, Vl, nv, qf, st, c, lane);
+  compute_tile<NT, MASK, LEAN>(Kl, Vl, nv, qf, st, c, lane);
 }
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -479,7 +562,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       const int s = s_lo + k;
       if (more && first) slice(k);
       if (active && s < gs)
-        compute_tile<NT>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, cur.L - (cur.t + s) * TK), qf, st,
+        compute_tile<NT, true, true>(lds + s * STAGE_B, lds + s * STAGE_B + TILE_B, min(TK, cur.L - (cur.t + s) * TK), qf, st,
                         F8 ? cu : P.c, lane);
       if (more && !first) slice(k);
     }
@@ -592,7 +675,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    compute_tile<1>(wlds, wlds + TILE_B, min(TK, cur.L - cur.t * TK), qf, st, F8 ? cu : P.c, lane);
+    compute_tile<1, true, true>(wlds, wlds + TILE_B, min(TK, cur.L - cur.t * TK), qf, st, F8 ? cu : P.c, lane);
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     if (!has_next || next_fresh)
@@ -1050,80 +1133,6 @@ __device__ __forceinline__ void score_products(const bf16x8 (&k)[4][2], const bf
       s1[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k[ks][1], qf[nt][ks], s1[nt], 0, 0, 0);
     }
 }
-// The softmax step on scores already in registers, in two halves (the V reads are issued between
-// them): the masked scores and the row maxima, then the weights, row sums and the rescaling.  Same
-// quotient sum(p v) / sum(p) as compute_tile, with less vector-ALU work per score, which this
-// kernel (unlike the memory-bound decode kernels) feels:
-//   * the score factor c goes into the exponent's fma instead of a multiply of its own;
-//   * maxima are taken as the median of (a, b, +inf): fmaxf has to return the other operand for a
-//     signalling NaN, for which the compiler first passes every operand it cannot prove quiet (a
-//     matrix-unit result, a cross-lane read) through an instruction of its own (the +inf comes
-//     through an empty asm so that the median is not folded back into fmaxf; no score is NaN here:
-//     keys past a row's limit are replaced by -inf before, and stores hold numbers);
-//   * the two cross-lane steps of a row maximum are gfx950's lane-swap instructions (rows of 16
-//     lanes, then halves of 32) instead of reads through the LDS queue;
-//   * a row's reference maximum moves only when a tile's maximum exceeds it by more than
-//     RESCALE_GAP powers of two (or on the row's first tile): until then the exponentials are taken
-//     against the stale maximum, are at most 2^RESCALE_GAP, and the 32 accumulator registers of a
-//     row block are left alone;
-//   * the sum of the bf16-rounded weights is a two-element dot product per register pair.
-constexpr float RESCALE_GAP = 8.f;
-__device__ __forceinline__ float max_raw(float a, float b) {
-  uint32_t inf = 0x7f800000u;
-  asm("" : "+s"(inf));
-  return __builtin_amdgcn_fmed3f(a, b, __uint_as_float(inf));
-}
-template <int NT, bool MASK>
-__device__ __forceinline__ void softmax_max(const f32x4 (&s0)[NT], const f32x4 (&s1)[NT], const int (&nvalid)[NT],
-                                            const WaveState<NT>& st, float c, int g, float (&sv)[NT][8], float (&m_new)[NT]) {
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      sv[nt][x] = (!MASK || 4 * g + x < nvalid[nt]) ? s0[nt][x] : -INFINITY;
-      sv[nt][4 + x] = (!MASK || 16 + 4 * g + x < nvalid[nt]) ? s1[nt][x] : -INFINITY;
-    }
-    float tmax = max_raw(max_raw(max_raw(sv[nt][0], sv[nt][1]), max_raw(sv[nt][2], sv[nt][3])),
-                         max_raw(max_raw(sv[nt][4], sv[nt][5]), max_raw(sv[nt][6], sv[nt][7])));
-    {
-      // swap(x, x) returns (x with its odd rows replaced by the even ones, x with its even rows replaced by
-      // the odd ones), resp. the same for the two halves of 32 lanes: their maximum is max(x[l], x[l ^ 16 or 32])
-      typedef unsigned int u32p __attribute__((ext_vector_type(2)));
-      const u32p a = __builtin_amdgcn_permlane16_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
-      tmax = max_raw(__uint_as_float(a[0]), __uint_as_float(a[1]));
-      const u32p b = __builtin_amdgcn_permlane32_swap(__float_as_uint(tmax), __float_as_uint(tmax), false, false);
-      tmax = max_raw(__uint_as_float(b[0]), __uint_as_float(b[1]));
-    }
-    m_new[nt] = max_raw(st.m[nt], tmax * c);
-  }
-}
-template <int NT>
-__device__ __forceinline__ void softmax_weights(const float (&sv)[NT][8], const float (&m_new)[NT], WaveState<NT>& st, bf16x8 (&pb)[NT], float c) {
-#pragma unroll
-  for (int nt = 0; nt < NT; ++nt) {
-    if (__any(m_new[nt] > st.m[nt] + RESCALE_GAP)) {         // first tile: -inf + gap = -inf
-      const float alpha = __builtin_amdgcn_exp2f(st.m[nt] - m_new[nt]);
-      st.l[nt] *= alpha;
-      st.lr[nt] *= alpha;
-#pragma unroll
-      for (int ct = 0; ct < 8; ++ct) st.O[nt][ct] *= alpha;
-      st.m[nt] = m_new[nt];
-    }
-    const float nm = -st.m[nt];
-    float se = 0.f, sr = 0.f;
-#pragma unroll
-    for (int x = 0; x < 8; x += 2) {
-      const float pe0 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x], c, nm));
-      const float pe1 = __builtin_amdgcn_exp2f(fmaf(sv[nt][x + 1], c, nm));
-      const bf16x2 pr = __builtin_convertvector(f32x2{pe0, pe1}, bf16x2);
-      pb[nt][x] = pr[0]; pb[nt][x + 1] = pr[1];
-      se += pe0 + pe1;
-      sr = __builtin_amdgcn_fdot2_f32_bf16(pr, bf16x2{static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)}, sr, false);
-    }
-    st.l[nt] += se;
-    st.lr[nt] += sr;
-  }
-}
 template <int NT>
 __device__ __forceinline__ void value_products(const s16x4 (&v)[8][2], const bf16x8 (&pb)[NT], WaveState<NT>& st) {
 #pragma unroll
@@ -1289,6 +1298,7 @@ Layout layout(const Problem& ds) {
 
 bool shared_supported(const Problem& ds) {
   if ((ds.dtype != RLDA_BF16 && ds.dtype != RLDA_BF16_KV8) || ds.d != D) return false;
+  if (!(ds.scale > 0.f)) return false;                                  // the tile routine's softmax takes maxima before scaling
   const int64_t B = (int64_t)ds.P * ds.G;
   const int r = ds.Hq / ds.Hkv;
   if (r > 16 || (int64_t)r * ds.G > MAX_GROUP_ROWS) return false;       // rows of one KV group: <= 4 parts of 64
@@ -1388,7 +1398,7 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, const int
   // block, and the register-staged kernel, so that there are enough workgroups for 256 compute units.
   const int rows1 = 16 * WG_WAVES;
   const int64_t units8 = (int64_t)8 * ceil_div(P_ * Hkv, 8);              // eight XCDs, whole rounds of units
-  const bool two = units8 * ceil_div(Lp_cap, (2 * rows1) / P.r) >= 4 * N_WG;
+  const bool two = units8 * ceil_div(Lp_cap, (2 * rows1) / P.r) >= 4 * N_WG && scale > 0.f;   // its softmax needs scale > 0
   P.QB = ((two ? 2 : 1) * rows1) / P.r;                     // query positions per workgroup
   P.nqb = ceil_div(Lp_cap, P.QB);
   typedef void (*kern_t)(const PrefillParams);

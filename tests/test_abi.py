@@ -64,6 +64,14 @@ def test_e4m3_store_dtype_is_planned_like_bf16():
     assert B.rl_decode_attn_plan(good(dtype=3)) == B.RLDA_ERR_UNSUPPORTED
 
 
+def test_only_positive_scales_are_planned_onto_the_shared_path():
+    assert B.rl_decode_attn_plan(good()) == B.RLDA_ALGO_SHARED
+    for sc in (0.0, -0.1, float("nan")):
+        assert B.rl_decode_attn_plan(good(scale=sc)) == B.RLDA_ALGO_SIMPLE
+        assert B.rl_decode_attn_plan(good(scale=sc, algo=B.RLDA_ALGO_SHARED)) == B.RLDA_ERR_UNSUPPORTED
+        assert B.rl_decode_attn_workspace_bytes(good(scale=sc)) == 0
+
+
 @pytest.mark.parametrize("kw,code", [
     (dict(d=96), B.RLDA_ERR_UNSUPPORTED),
     (dict(d=256), B.RLDA_ERR_UNSUPPORTED),

@@ -380,3 +380,19 @@ def test_rows_with_many_parts_in_the_16_lane_combine(B, paged):
     torch.cuda.synchronize()
     ro, rl = util.oracle_paged(y, 0.1, G)
     util.compare(out, lse, ro, rl, "bf16", "many parts, paged")
+
+
+@pytest.mark.parametrize("scale", [-0.09, 0.0])
+def test_non_positive_scale_runs_on_the_simple_kernel(B, scale):
+    """The shared-prefix path takes its row maxima before scaling and therefore positive scales only; anything
+    else (anti-attention, a uniform average) is planned onto the simple kernel, with the same result."""
+    import torch
+    x = util.random_case(91, 3, 4, 8, 2, 128, 150, 90, "bf16")
+    t = util.to_device(x)
+    out = torch.empty((12, 8, 128), dtype=torch.float32, device="cuda:0")
+    ds = B.desc_from_tensors(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_suffix"], t["v_suffix"],
+                             t["suffix_lens"], scale, 4, out, None)
+    assert B.rl_decode_attn_plan(ds) == B.RLDA_ALGO_SIMPLE
+    check(x, scale, 4, "bf16", "auto", f"scale {scale}", B)
+    with pytest.raises(B.RldaError):
+        util.gpu_run(t, scale, 4, algo=B.RLDA_ALGO_SHARED)

@@ -136,3 +136,10 @@ def test_vlm7b_prompt_shape_on_sampled_rows(B):
     assert eo <= 1e-2 and el <= 1e-3
     ro7, rl7 = prefill_attn_ref(x["q"][7:], x["k"][7:], x["v"][7:], x["lens"][7:], w.scale)
     assert np.abs(out[7] - ro7[0]).max() <= 1e-2 and np.abs(lse[7] - rl7[0]).max() <= 1e-3
+
+
+@pytest.mark.parametrize("scale", [-0.07, 0.0])
+def test_non_positive_scale(B, scale):
+    # large enough for the 128-row kernel, whose softmax needs a positive scale: such calls take the other kernel
+    x = case(77, 100, 330, 14, 2)
+    check(B, x, scale, f"scale {scale}")
