@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "87c9493db7cf9087ec88556b8403b3a2af9ffe946201bc0aff6a250ef1093fb6",
-    "fetch_bytes": 623801353,
-    "write_bytes": 9339888,
+    "csrc_sha256": "ea143910dff97ac9612316d2e7c708360395e99d205426753d88fe02ef065d17",
+    "fetch_bytes": 623802817,
+    "write_bytes": 9342100,
 }
 
 
