@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "ea143910dff97ac9612316d2e7c708360395e99d205426753d88fe02ef065d17",
+    "csrc_sha256": "0d3664da045a259b9ef213e54372a0500da72b87bca553701e67daa1e3759688",
     "fetch_bytes": 623802817,
     "write_bytes": 9342100,
 }

@@ -1394,15 +1394,16 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, const int
   P.c = scale * 1.4426950408889634f;
   // Two 16-row blocks per wavefront (128 rows per workgroup) amortise every LDS read, barrier and
   // tile over twice the matrix work (measured with the register-staged kernel: 440 -> 514 Tflop/s on
-  // 32 prompts of 1280 tokens; prefill2_kernel, which they run on: 592); small problems keep one
-  // block, and the register-staged kernel, so that there are enough workgroups for 256 compute units.
+  // 32 prompts of 1280 tokens; prefill2_kernel, which they run on: 592, then 688 with its leaner softmax);
+  // small problems keep one block so that there are enough workgroups for 256 compute units.  The
+  // register-staged kernel is what scales that are not positive run on.
   const int rows1 = 16 * WG_WAVES;
   const int64_t units8 = (int64_t)8 * ceil_div(P_ * Hkv, 8);              // eight XCDs, whole rounds of units
   const bool two = units8 * ceil_div(Lp_cap, (2 * rows1) / P.r) >= 4 * N_WG && scale > 0.f;   // its softmax needs scale > 0
   P.QB = ((two ? 2 : 1) * rows1) / P.r;                     // query positions per workgroup
   P.nqb = ceil_div(Lp_cap, P.QB);
   typedef void (*kern_t)(const PrefillParams);
-  const kern_t kern = two ? prefill2_kernel<2> : prefill_kernel<1>;
+  const kern_t kern = two ? prefill2_kernel<2> : (scale > 0.f ? prefill2_kernel<1> : prefill_kernel<1>);
   {
     static std::mutex mu;
     static bool done[64] = {};
@@ -1411,7 +1412,7 @@ hipError_t launch_prefill(const void* q, const void* k, const void* v, const int
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (const kern_t kf : {static_cast<kern_t>(prefill_kernel<1>), static_cast<kern_t>(prefill2_kernel<2>)}) {
+      for (const kern_t kf : {static_cast<kern_t>(prefill_kernel<1>), static_cast<kern_t>(prefill2_kernel<2>), static_cast<kern_t>(prefill2_kernel<1>)}) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kf), hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }
