@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "0d3664da045a259b9ef213e54372a0500da72b87bca553701e67daa1e3759688",
-    "fetch_bytes": 623802817,
-    "write_bytes": 9342100,
+    "csrc_sha256": "7992b204418b8bb69cf114e0a7f34df2c05040fb9e682e860925b8d1edcba0cc",
+    "fetch_bytes": 625144013,
+    "write_bytes": 9339752,
 }
 
 
