@@ -34,9 +34,9 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "7992b204418b8bb69cf114e0a7f34df2c05040fb9e682e860925b8d1edcba0cc",
-    "fetch_bytes": 625144013,
-    "write_bytes": 9339752,
+    "csrc_sha256": "04b5159cd23a20f6a01b928e32b2cb9c1e7343bf7ebc15dcb48356d153047731",
+    "fetch_bytes": 623802817,
+    "write_bytes": 9342100,
 }
 
 

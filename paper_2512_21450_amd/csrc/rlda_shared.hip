@@ -357,10 +357,11 @@ __device__ __forceinline__ void write_partial(const WaveState<NT>& st, _Float16*
 }
 
 __device__ __forceinline__ u32x4 ldg16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
-// Suffix K/V rows are read exactly once per call: stream them past the caches.  (Prefix tiles take ordinary
-// loads: a KV group of more than 64 rows reads each of them once per row part, the second time from L2, and
-// the two workgroups of a pair meet in the same tiles at their boundary; measured 160 -> 150 us per step on
-// the 128-row workload, 114.8 -> 112.7 on the 56-row one.)
+// K/V rows that are read exactly once per call are streamed past the caches: all suffix tiles, and the prefix
+// tiles of KV groups of at most 64 rows.  A larger group reads each prefix tile once per row part; with ordinary
+// loads the second read is served by the memory-side cache (160 -> 150 us per step on the 128-row workload).
+// (For single-part groups ordinary prefix loads only help a benchmark that returns to the same prefix within
+// the 256 MB of that cache; with more K/V in rotation they cost 1 %.)
 __device__ __forceinline__ u32x4 ldg16_stream(const char* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
 }
@@ -466,7 +467,7 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, in
 // memory pipeline and the matrix pipeline of the CU overlap and no bubble opens at a unit
 // boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
 // merged through LDS and the partial is written.
-template <int NRB, int NT, bool EXT, bool F8>
+template <int NRB, int NT, bool EXT, bool F8, bool REREAD>
 __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int tid) {
   auto len_of = [&](int p) { return plen_of<EXT>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
@@ -478,6 +479,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int lrow = St::lrow(lane), chunk = St::chunk(lane);
   auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
   auto head_of = [&](const Cur& c) { return c.j >> P.NHs; };
+  constexpr bool reread = REREAD;                           // every prefix tile is read once per row part: keep it cached
   char* mine = lds + wv * STAGE_B;
 
   constexpr bool QPRE = NT == 1;                            // query rows of the next unit are prefetched (one block per wavefront)
@@ -510,8 +512,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       const size_t off = (size_t)(key0 + min(St::RS * i + lrow, last)) * GROWB + 16 * chunk;
-      rk[i] = ldg16(kb + off);
-      rv[i] = ldg16(vb + off);
+      if constexpr (reread) { rk[i] = ldg16(kb + off); rv[i] = ldg16(vb + off); }
+      else                  { rk[i] = ldg16_stream(kb + off); rv[i] = ldg16_stream(vb + off); }
     }
   }
   bool fresh = true;
@@ -555,8 +557,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       for (int i = 0; i < NL; ++i) {                        // rows past the length re-read the last real row
         if (i >= k * LPS && i < (k + 1) * LPS) {
           const size_t off = (size_t)(key0 + min(St::RS * i + lrow, last)) * GROWB + 16 * chunk;
-          rk[i] = ldg16(kb + off);
-          rv[i] = ldg16(vb + off);
+          if constexpr (reread) { rk[i] = ldg16(kb + off); rv[i] = ldg16(vb + off); }
+          else                  { rk[i] = ldg16_stream(kb + off); rv[i] = ldg16_stream(vb + off); }
         }
       }
     };
@@ -688,7 +690,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   }
 }
 
-template <int NRB, int NT, bool EXT, bool F8>
+template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false>   // REREAD: KV groups of several row parts (NRB = 4)
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -744,7 +746,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
     cur_load(c, [&](int p) { return plen_of<EXT>(P, p); });
-    prefix_stream<NRB, NT, EXT, F8>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
+    prefix_stream<NRB, NT, EXT, F8, REREAD>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
@@ -1343,12 +1345,16 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   const bool f8 = ds.dtype == RLDA_BF16_KV8;
   P.kscale = f8 ? ds.k_scale : nullptr; P.vscale = f8 ? ds.v_scale : nullptr;
   typedef void (*kern_t)(const SharedParams);
-  static const kern_t kerns[12] = {       // [e4m3 store][extended form][row blocks 1, 2, 4]
+  static const kern_t kerns[16] = {       // [e4m3 store][extended form][row blocks 1, 2, 4], then the
+                                          // four-block kernels of groups with several row parts: [e4m3][extended]
       partial_kernel<1, 1, false, false>, partial_kernel<2, 1, false, false>, partial_kernel<4, 1, false, false>,
       partial_kernel<1, 1, true, false>,  partial_kernel<2, 1, true, false>,  partial_kernel<4, 1, true, false>,
       partial_kernel<1, 1, false, true>,  partial_kernel<2, 1, false, true>,  partial_kernel<4, 1, false, true>,
-      partial_kernel<1, 1, true, true>,   partial_kernel<2, 1, true, true>,   partial_kernel<4, 1, true, true>};
-  const kern_t kern = kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
+      partial_kernel<1, 1, true, true>,   partial_kernel<2, 1, true, true>,   partial_kernel<4, 1, true, true>,
+      partial_kernel<4, 1, false, false, true>, partial_kernel<4, 1, true, false, true>,
+      partial_kernel<4, 1, false, true, true>,  partial_kernel<4, 1, true, true, true>};
+  const kern_t kern = P.NH > 1 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
+                               : kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
   // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
   {
     static std::mutex mu;
@@ -1358,7 +1364,7 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (int i = 0; i < 12; ++i) {
+      for (int i = 0; i < 16; ++i) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
