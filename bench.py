@@ -34,7 +34,7 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # compared from the compiler's assembly output, are unchanged).
 PMC_TRAFFIC = {
     "workload": "vlm7b",
-    "csrc_sha256": "04b5159cd23a20f6a01b928e32b2cb9c1e7343bf7ebc15dcb48356d153047731",
+    "csrc_sha256": "2dc040cefcb1eefb065341a988f32566a17d36dade0daaf85986c464d980b913",
     "fetch_bytes": 623802817,
     "write_bytes": 9342100,
 }

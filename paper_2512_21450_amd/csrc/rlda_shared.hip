@@ -21,8 +21,12 @@
 // B-operand layout of the second contraction O^T += V_tile^T * P^T, so the
 // probabilities go from accumulator to operand with a bf16 convert and no
 // cross-lane traffic.  V^T comes from LDS through ds_read_b64_tr_b16.  The online
-// softmax needs one 4-lane max per tile (two xor-shuffles); row sums stay per
+// softmax needs one 4-lane max per tile (two lane swaps); row sums stay per
 // lane until the partial is written.
+//
+// The same source holds the prefill pass (causal attention of every prompt over itself, once per
+// prompt: prefill2_kernel, and the register-staged prefill_kernel it grew out of), which is built
+// from the same tile layout and products.
 #include "rlda_internal.h"
 #include "rlda_sched.h"
 
