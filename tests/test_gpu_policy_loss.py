@@ -151,3 +151,12 @@ def test_group_advantage(B, mode, P, G, M):
             assert (adv[:G] == 0).all(), "equal rewards must give exactly zero advantages"
         else:
             assert (adv == 0).all()
+
+
+def test_policy_loss_many_short_sequences(B):
+    # more than 4096 sequences: the batch totals come from a launch of their own instead of from every workgroup
+    x = wl.make_rollout_tokens(5000, 48, 8, seed=41, lens=("uniform", 48))
+    x["lens"][::7] = 0
+    _, adv = group_advantage_ref(x["metrics"], x["weights"], 8)
+    for agg in (0, 1):
+        check_loss(B, x, adv.astype(np.float32), 0.2, 0.25, beta_kl=0.03, beta_ent=0.01, agg=agg)
