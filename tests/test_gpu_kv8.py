@@ -162,6 +162,22 @@ def test_paged_store_with_finished_sequences(page_size, B):
         util.compare(out, lse, ro, rl, "bf16", f"paged {page_size} {a is not None}")
 
 
+@pytest.mark.parametrize("G,Hq,Hkv", [(16, 16, 2), (32, 14, 2)])
+def test_paged_store_with_several_row_parts(G, Hq, Hkv, B):
+    """KV groups of 128 and 224 rows (two and four row parts) on a paged e4m3 store with finished sequences:
+    the kernel variant that keeps the prefix tiles cached between the parts, in its extended e4m3 form."""
+    import torch
+    P, d = 3, 128
+    x = kv8_case(23 + G, P, G, Hq, Hkv, d, 170, 260)
+    y = wl.to_pages(x, 64, seed=5)
+    act = (np.arange(P * G) % 4 != 2).astype(np.uint8)
+    t = util.to_device(y)
+    for a in (None, act):
+        out, lse = util.gpu_run_paged(t, 0.088, G, active=None if a is None else torch.from_numpy(a).cuda())
+        ro, rl = util.oracle_paged(y, 0.088, G, active=a)
+        util.compare(out, lse, ro, rl, "bf16", f"paged G{G} {a is not None}")
+
+
 def test_bitwise_determinism_and_store_independence(B):
     import torch
     x = kv8_case(31, 4, 8, 28, 4, 128, 300, 500)
