@@ -175,6 +175,20 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
+    # what a plain device-to-device copy of 1 GiB moves on this machine (bytes read + bytes written per second):
+    # context for the published peak the roofline is priced against
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(5):
+        b.copy_(a)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * float(1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a, b
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -301,7 +315,8 @@ def main():
                      "kernel": "partial_kernel" if plan == 2 else "simple_kernel",
                      "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
                      "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),
-                     "rest_of_step_us_mean": float(rest_ms.mean() * 1e3)},
+                     "rest_of_step_us_mean": float(rest_ms.mean() * 1e3),
+                     "plain_copy_GBps_on_this_box": copy_gbps},
         "cpu_baseline": cpu,
         "naive_gpu_baseline": naive,
         "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
