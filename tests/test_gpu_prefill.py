@@ -75,9 +75,11 @@ def test_reduced_sizes(B, case_):
     check(B, x, 1.0 / math.sqrt(128), str(case_))
 
 
-@pytest.mark.parametrize("P,L,Hq,Hkv", [(64, 400, 12, 4), (100, 330, 14, 2), (33, 500, 16, 16)])
+@pytest.mark.parametrize("P,L,Hq,Hkv", [(64, 400, 12, 4), (100, 330, 14, 2), (33, 500, 16, 16), (48, 200, 32, 2),
+                                         (96, 300, 10, 2), (64, 260, 16, 2)])
 def test_many_prompts_take_the_two_block_kernel(B, P, L, Hq, Hkv):
-    # enough workgroups for the variant with 128 rows per workgroup (r = 3, 7, 1: 42, 18, 128 positions per block)
+    # enough workgroups for the variant with 128 rows per workgroup (r = 3, 7, 1, 16, 5, 8: 42, 18, 128, 8, 25, 16
+    # positions per block)
     x = case(900 + P, P, L, Hq, Hkv)
     x["lens"][:3] = [L, 1, 0]
     check(B, x, 1.0 / math.sqrt(128), f"P{P} L{L} {Hq}/{Hkv}")
