@@ -148,6 +148,27 @@ size_t rl_decode_attn_workspace_bytes(const rlda_desc* desc);
  */
 int rl_decode_attn_plan(const rlda_desc* desc);
 
+/*
+ * rl_decode_attn for callers that cannot allocate or carry device memory of
+ * their own for the library's scratch: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments, result
+ * (bit for bit), stream and error behaviour as rl_decode_attn, except that
+ * desc->workspace and desc->workspace_bytes are ignored: the scan of tile
+ * counts and the partial results go to an array of
+ * RLDA_STATIC_WORKSPACE_BYTES that is part of the library's device image
+ * (every GPU the process uses holds one copy until the process ends).  The
+ * call allocates and frees nothing, on the host or on the device.  A problem
+ * whose rl_decode_attn_workspace_bytes exceeds the array returns
+ * RLDA_ERR_WORKSPACE and enqueues nothing.  All calls on one GPU share that
+ * GPU's array: calls that may overlap in time there (different streams, or
+ * graphs replayed concurrently) race on it and must be ordered by the caller;
+ * nothing needs to be cleared between calls (the kernels write every entry
+ * they later read).
+ */
+#define RLDA_STATIC_WORKSPACE_BYTES (64u << 20)
+int    rl_decode_attn_static(const rlda_desc* desc, void* hip_stream);
+size_t rl_decode_attn_static_workspace_limit(void);          /* = RLDA_STATIC_WORKSPACE_BYTES; pure host */
+
 /* Static, NUL-terminated description of a return code. */
 const char* rl_decode_attn_strerror(int code);
 

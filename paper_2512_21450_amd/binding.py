@@ -80,6 +80,10 @@ _lib.rl_decode_attn_paged_plan.restype = ctypes.c_int
 _lib.rl_decode_attn_paged_plan.argtypes = [_pp]
 _lib.rl_decode_attn.restype = ctypes.c_int
 _lib.rl_decode_attn.argtypes = [_dp, ctypes.c_void_p]
+_lib.rl_decode_attn_static.restype = ctypes.c_int
+_lib.rl_decode_attn_static.argtypes = [_dp, ctypes.c_void_p]
+_lib.rl_decode_attn_static_workspace_limit.restype = ctypes.c_size_t
+_lib.rl_decode_attn_static_workspace_limit.argtypes = []
 _lib.rl_decode_attn_profiled.restype = ctypes.c_int
 _lib.rl_decode_attn_profiled.argtypes = [_dp, ctypes.c_void_p, ctypes.c_void_p]
 _lib.rl_decode_attn_workspace_bytes.restype = ctypes.c_size_t
@@ -144,6 +148,15 @@ def rl_decode_attn_raw(desc: rlda_desc, stream_handle=None) -> int:
 def rl_decode_attn_profiled(desc: rlda_desc, stream_handle, mid_event_handle) -> int:
     """Direct call that also records ``mid_event_handle`` after the K/V-streaming kernel."""
     return _lib.rl_decode_attn_profiled(ctypes.byref(desc), stream_handle, mid_event_handle)
+
+
+def rl_decode_attn_static_raw(desc: rlda_desc, stream_handle=None) -> int:
+    """Direct call of the entry point that uses the library's own scratch array; returns the C return code."""
+    return _lib.rl_decode_attn_static(ctypes.byref(desc), stream_handle)
+
+
+def rl_decode_attn_static_workspace_limit() -> int:
+    return _lib.rl_decode_attn_static_workspace_limit()
 
 
 def _torch_dtype_code(t):
@@ -219,6 +232,21 @@ def rl_decode_attn(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffi
             ds.workspace, ds.workspace_bytes = workspace.data_ptr(), need
     s = stream if stream is not None else torch.cuda.current_stream(q.device)
     rc = _lib.rl_decode_attn(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse
+
+
+def rl_decode_attn_static(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
+                          out, lse=None, algo=RLDA_ALGO_AUTO, stream=None, k_scale=None, v_scale=None):
+    """rl_decode_attn without any allocation: ``out`` (and ``lse``) are the caller's, the scratch is the library's."""
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_decode_attn_static needs device tensors; there is no CPU path")
+    ds = desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
+                           out, lse, None, algo, k_scale, v_scale)
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_decode_attn_static(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
     if rc != RLDA_OK:
         raise RldaError(rc)
     return out, lse

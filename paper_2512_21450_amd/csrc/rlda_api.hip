@@ -5,6 +5,7 @@
 #include "rlda_sched.h"
 #include "../../include/rl_prefill_attn.h"
 
+#include <mutex>
 #include <vector>
 
 namespace {
@@ -85,15 +86,22 @@ size_t workspace_of(const Desc* desc) {
 
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
-int enqueue(const Problem& pb, void* hip_stream, void* mid_event) {
-  const int pl = plan(pb);
-  if (pl < 0) return pl;
+// the tensors a non-empty batch needs
+int check_pointers(const Problem& pb) {
   const int64_t B = (int64_t)pb.P * pb.G;
   if (B > 0 && (!pb.q || !pb.prefix_lens || !pb.suffix_lens || !pb.out)) return RLDA_ERR_INVALID;
   if (pb.P > 0 && pb.Lp_cap > 0 && (!pb.k_prefix || !pb.v_prefix)) return RLDA_ERR_INVALID;
   if (B > 0 && pb.Ls_cap > 0 && (!pb.k_suffix || !pb.v_suffix)) return RLDA_ERR_INVALID;
   if (B > 0 && pb.max_pages > 0 && !pb.block_table) return RLDA_ERR_INVALID;
-  if (B == 0) return RLDA_OK;
+  return RLDA_OK;
+}
+
+int enqueue(const Problem& pb, void* hip_stream, void* mid_event) {
+  const int pl = plan(pb);
+  if (pl < 0) return pl;
+  const int rc = check_pointers(pb);
+  if (rc != RLDA_OK) return rc;
+  if ((int64_t)pb.P * pb.G == 0) return RLDA_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
   if (pl == RLDA_ALGO_SHARED) {
@@ -114,6 +122,56 @@ int enqueue_of(const Desc* desc, void* hip_stream, void* mid_event) {
   Problem pb;
   const int rc = to_problem(desc, pb);
   return rc != RLDA_OK ? rc : enqueue(pb, hip_stream, mid_event);
+}
+
+// ---- rl_decode_attn_static: the same step for callers that cannot bring (or allocate) a workspace.
+// The scan of tile counts and the partial results live in this file-scope device array instead.
+// Every GPU the library runs on holds its own copy at its own address until the process ends; the
+// array's name is only a host-side stand-in for it, so the address is asked for once per device
+// (with that device current) and kept.
+__device__ __align__(256) unsigned char g_static_workspace[RLDA_STATIC_WORKSPACE_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[MAX_DEVICES] = {};
+
+hipError_t static_workspace(void** ptr) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_workspace));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_static_ptr[dev] = p;
+  }
+  *ptr = g_static_ptr[dev];
+  return hipSuccess;
+}
+
+int enqueue_static(const rlda_desc* desc, void* hip_stream) {
+  Problem pb;
+  const int rc = to_problem(desc, pb);
+  if (rc != RLDA_OK) return rc;
+  pb.workspace = nullptr; pb.workspace_bytes = 0;           // the descriptor's own workspace fields are not used
+  const int pl = plan(pb);
+  if (pl < 0) return pl;
+  if (pl == RLDA_ALGO_SHARED) {
+    const size_t need = rlda::shared_workspace_bytes(pb);
+    if (need > (size_t)RLDA_STATIC_WORKSPACE_BYTES) return RLDA_ERR_WORKSPACE;
+    const int rp = check_pointers(pb);                       // before the device is asked for anything
+    if (rp != RLDA_OK) return rp;
+    if ((int64_t)pb.P * pb.G > 0) {
+      void* p = nullptr;
+      const hipError_t e = static_workspace(&p);
+      if (e != hipSuccess) { g_last_hip_error = e; return RLDA_ERR_LAUNCH; }
+      pb.workspace = p; pb.workspace_bytes = RLDA_STATIC_WORKSPACE_BYTES;
+    }
+  }
+  return enqueue(pb, hip_stream, nullptr);
 }
 
 }  // namespace
@@ -142,6 +200,9 @@ int rl_decode_attn(const rlda_desc* desc, void* hip_stream) { return enqueue_of(
 int rl_decode_attn_profiled(const rlda_desc* desc, void* hip_stream, void* mid_event) {
   return enqueue_of(desc, hip_stream, mid_event);
 }
+
+int rl_decode_attn_static(const rlda_desc* desc, void* hip_stream) { return enqueue_static(desc, hip_stream); }
+size_t rl_decode_attn_static_workspace_limit(void) { return RLDA_STATIC_WORKSPACE_BYTES; }
 
 int rl_decode_attn_paged_plan(const rlda_paged_desc* desc) { return plan_of(desc); }
 size_t rl_decode_attn_paged_workspace_bytes(const rlda_paged_desc* desc) { return workspace_of(desc); }

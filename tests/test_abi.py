@@ -305,3 +305,19 @@ def test_prefill_descriptor_layout_and_errors():
     ds = mk(**ptrs); ds.struct_size = 4
     assert B.rl_prefill_attn_raw(ds) == -4
     assert B._lib.rl_prefill_attn(None, None) == -1
+
+
+def test_static_entry_point_validates_on_the_host_and_knows_its_limit():
+    lim = B.rl_decode_attn_static_workspace_limit()
+    assert lim == 64 << 20
+    # a problem whose partial results do not fit the library's own array: refused before anything is enqueued
+    huge = good(P=900, G=16, Hq=32, Hkv=2, Lp_cap=64, Ls_cap=64)
+    assert B.rl_decode_attn_plan(huge) == B.RLDA_ALGO_SHARED
+    assert B.rl_decode_attn_workspace_bytes(huge) > lim
+    assert B.rl_decode_attn_static_raw(huge) == B.RLDA_ERR_WORKSPACE
+    assert B.rl_decode_attn_static_raw(good(d=96)) == B.RLDA_ERR_UNSUPPORTED
+    bad = good()
+    bad.struct_size = 8
+    assert B.rl_decode_attn_static_raw(bad) == B.RLDA_ERR_STRUCT_SIZE
+    assert B.rl_decode_attn_static_raw(good()) == B.RLDA_ERR_INVALID     # fits, but q / lengths / out are NULL
+    assert B.rl_decode_attn_static_raw(good(P=0)) == B.RLDA_OK           # empty batch: nothing to do
