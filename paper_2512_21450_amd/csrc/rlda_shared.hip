@@ -43,6 +43,7 @@ constexpr int STAGE_B = 2 * TILE_B;               // K tile + V tile
 constexpr int NTHREADS = 64 * WG_WAVES;
 constexpr int LDS_BYTES = WG_WAVES * STAGE_B;     // 64 KB: one stage per wavefront, two workgroups per CU
 constexpr int MAX_SCAN = LDS_BYTES / 4;           // ints of LDS available to the length scan
+constexpr int N_XCD = 8;                          // compute dies; workgroup i is dispatched to die i % N_XCD
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -628,9 +629,10 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
 // ---- suffix tiles of one wavefront: `n` tiles of the line starting at `cur`, streamed through the
 // wavefront's private 16 KB of LDS.  The loads of tile i + 1 (and the query rows of its unit when
 // it starts a new one) are in flight while tile i is computed, across unit boundaries as well.
+// `flush`: this wavefront writes its die's L2 back once its first tile has landed, see below.
 template <bool EXT, bool F8>
 __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds, Cur cur, int n, int slot_base,
-                                              int lane) {
+                                              int lane, bool flush) {
   auto len_of = [&](int b) { return slen_of<EXT>(P, b); };
   using St = Stage<F8>;
   constexpr int NL = St::NL, GROWB = St::GROWB;
@@ -663,6 +665,17 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   };
   issue_q(cur);
   issue_tile(cur);
+  // The partial rows stored so far sit in this die's L2 as dirty lines.  Left alone they trickle out one
+  // by one under the read stream, and such lone write-backs cost the stream far more than their bytes
+  // (measured at the 7B shape: the K/V stream runs at 6.2 TB/s for the rest of the kernel once the
+  // workgroups have stored their prefix partials, against 7.0-7.5 TB/s when the lines are written back
+  // in one go; stores that write through cost more than that single write-back).  An agent-scope
+  // release is that write-back; one wavefront per die issues it (more than one per die only adds cost),
+  // a tile's round trip after its own workgroup's prefix partial.
+  if (flush) {
+    wait_vmem();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+  }
   bool fresh = true;
   for (int i = 0; i < n; ++i) {
     wait_vmem();
@@ -755,7 +768,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
     cur_load(c, [&](int b) { return slen_of<EXT>(P, b); });
-    suffix_stream<EXT, F8>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane);
+    // Workgroup i runs on die i % N_XCD.  The first wavefront of the first workgroup on each die writes that
+    // die's L2 back when its first suffix tile has landed: the workgroups of the die have stored their prefix
+    // partials by then (all carry the same number of prefix tiles).  A wrong guess about which die a workgroup
+    // is on only makes the write-back less useful.
+    suffix_stream<EXT, F8>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane,
+                           ilo < ihi && w < N_XCD && wv == 0);
   }
 }
 
@@ -972,7 +990,7 @@ template <int NTP>                                          // 16-row blocks per
 __global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  constexpr int N_XCD = 8, WROWS = 16 * NTP;                // rows per wavefront
+  constexpr int WROWS = 16 * NTP;                           // rows per wavefront
   const int units = P.P * P.Hkv;
   const int xcd = blockIdx.x % N_XCD, seq = blockIdx.x / N_XCD;
   const int pj = (seq / P.nqb) * N_XCD + xcd, qb = P.nqb - 1 - seq % P.nqb;
@@ -1161,7 +1179,7 @@ template <int NTP>
 __global__ void __launch_bounds__(NTHREADS, 2) prefill2_kernel(const PrefillParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  constexpr int N_XCD = 8, WROWS = 16 * NTP;
+  constexpr int WROWS = 16 * NTP;
   const int units = P.P * P.Hkv;
   const int xcd = blockIdx.x % N_XCD, seq = blockIdx.x / N_XCD;
   const int pj = (seq / P.nqb) * N_XCD + xcd, qb = P.nqb - 1 - seq % P.nqb;
