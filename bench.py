@@ -26,18 +26,17 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
-# HBM bytes one launch of the K/V-streaming kernel moved, from two rocprofv3 --pmc passes
-# (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read
-# for the 1 GiB copy of --copy-probe (profiles/partial_kernel_vlm7b_hbm_traffic.md).  Only
-# valid for the workload and the kernel sources the counters were taken on (the hash below is
-# re-stamped after edits to those files only when the decode kernels' instruction streams,
-# compared from the compiler's assembly output, are unchanged).
+# HBM bytes one launch of the K/V-streaming kernel moved, per workload, from two rocprofv3 --pmc passes
+# (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read for the
+# 1 GiB copy of --copy-probe (profiles/partial_kernel_*_hbm_traffic.md).  Carried over from that profile
+# run, not measured in this one: reported only while the sources the kernel is built from still hash to
+# what the counters were taken on, null otherwise.
 PMC_TRAFFIC = {
-    "workload": "vlm7b",
-    "csrc_sha256": "2dc040cefcb1eefb065341a988f32566a17d36dade0daaf85986c464d980b913",
-    "fetch_bytes": 623802817,
-    "write_bytes": 9342100,
+    "csrc_sha256": "",
+    "vlm7b": {"fetch_bytes": 0, "write_bytes": 0},
 }
+
+OTHER_WORKLOADS = ("tiny", "vlm3b", "agentic", "highbatch")     # reported beside the default one, in short form
 
 
 def csrc_sha256():
@@ -51,69 +50,65 @@ def csrc_sha256():
 
 
 def measured_traffic(workload, plan):
-    """Counter-measured HBM bytes per launch, or None when they do not describe this run."""
-    if workload != PMC_TRAFFIC["workload"] or plan != 2 or csrc_sha256() != PMC_TRAFFIC["csrc_sha256"]:
+    """Counter-measured HBM bytes per launch (carried over from the profile run), or None when they do
+    not describe this run."""
+    t = PMC_TRAFFIC.get(workload)
+    if not t or plan != 2 or not t["fetch_bytes"] or csrc_sha256() != PMC_TRAFFIC["csrc_sha256"]:
         return None
-    return PMC_TRAFFIC["fetch_bytes"] + PMC_TRAFFIC["write_bytes"]
+    return t["fetch_bytes"] + t["write_bytes"]
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="vlm7b", help="tiny | vlm3b | vlm7b | agentic | highbatch")
-    ap.add_argument("--algo", default="auto", choices=["auto", "simple", "shared"])
-    ap.add_argument("--sets", type=int, default=3, help="rotating copies of the KV tensors")
-    ap.add_argument("--event-every", type=int, default=8, help="record per-kernel HIP events on every n-th step")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
-    ap.add_argument("--kv", default="bf16", choices=["bf16", "e4m3"],
-                    help="element type of the K/V stores (e4m3: one byte per element plus a factor per KV head; "
-                         "q and the arithmetic stay bf16)")
-    ap.add_argument("--naive-steps", type=int, default=20,
-                    help="steps of the unoptimised GPU kernel timed as a reference row (0 = skip)")
-    ap.add_argument("--page-size", type=int, default=0,
-                    help="0: contiguous suffix store (the headline configuration); else rows per page of a paged store")
-    ap.add_argument("--finished", type=float, default=0.0,
-                    help="fraction of sequences marked finished (paged store only)")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
-    ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss", "prefill"],
-                    help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel; "
-                         "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens; "
-                         "prefill: causal attention of the workload's prompts over themselves")
-    ap.add_argument("--tokens", type=int, default=1024, help="policy_loss: token capacity per sequence")
-    ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
-    ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
-    ap.add_argument("--no-ref", action="store_true", help="token_logprob: no reference logits (no KL)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this is a single-GPU kernel library; only --gpus 1 is supported "
-              "(the path shards by prompt group with no exchange, nothing to measure across GPUs here)",
-              file=sys.stderr)
-        sys.exit(2)
+def stats_us(ms):
+    """median / min / p90 of a list of millisecond samples, in microseconds"""
+    a = np.asarray(ms, dtype=np.float64) * 1e3
+    return {"median": float(np.median(a)), "min": float(a.min()), "p90": float(np.percentile(a, 90)), "n": int(a.size)}
 
-    import torch
-    from paper_2512_21450_amd import binding as B
-    from paper_2512_21450_amd import workloads as wl
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    if args.op == "token_logprob":
-        return bench_token_logprob(args, torch, B, wl, dev)
-    if args.op == "policy_loss":
-        return bench_policy_loss(args, torch, B, wl, dev)
-    if args.op == "prefill":
-        return bench_prefill(args, torch, B, wl, dev)
-    w = wl.WORKLOADS[args.workload]
+def streaming_read_ceiling(torch, dev, stream):
+    """GB/s of a loads-only kernel with the K/V-streaming kernel's access pattern (a measurement aid built
+    into a shared object of its own), over three rotating 1 GiB buffers: the rate the memory system delivers
+    to this kind of reader, next to the published peak the roofline is priced against."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2512_21450_amd", "libbench_stream_read.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.bench_stream_read.restype = ctypes.c_int
+    lib.bench_stream_read.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
+    lib.bench_stream_read_bytes.restype = ctypes.c_size_t
+    lib.bench_stream_read_bytes.argtypes = [ctypes.c_size_t]
+    n = 1 << 30
+    bufs = [torch.zeros(n, dtype=torch.uint8, device=dev) for _ in range(3)]
+    sink = torch.zeros(4096, dtype=torch.int32, device=dev)
+    sh = ctypes.c_void_p(stream.cuda_stream)
+    moved = lib.bench_stream_read_bytes(n)
+
+    def go(i):
+        rc = lib.bench_stream_read(bufs[i % 3].data_ptr(), n, sink.data_ptr(), sh)
+        if rc != 0:
+            raise RuntimeError(f"bench_stream_read failed ({rc})")
+    for i in range(3):
+        go(i)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(15)]
+    for i, (a, b) in enumerate(ev):
+        a.record(stream); go(i); b.record(stream)
+    torch.cuda.synchronize()
+    ms = np.median([a.elapsed_time(b) for a, b in ev])
+    del bufs
+    return moved / (ms * 1e-3) / 1e9
+
+
+def run_decode(args, torch, B, wl, dev, wname, steps, warmup, event_calls, full):
+    """One workload: K timed steps (wall clock, back to back), then `event_calls` calls bracketed by HIP
+    events on the launch stream (the library records one more between its two kernels), then the parity
+    check on sampled rows.  `full`: also the CPU-oracle and unoptimised-GPU reference rows."""
+    w = wl.WORKLOADS[wname]
     algo = {"auto": B.RLDA_ALGO_AUTO, "simple": B.RLDA_ALGO_SIMPLE, "shared": B.RLDA_ALGO_SHARED}[args.algo]
 
     x = wl.make_inputs(w, threads=16)
-    kv8 = args.kv == "e4m3"
+    kv8 = args.kv == "e4m3" and w.dtype == "bf16"
     if kv8:
-        if w.dtype != "bf16":
-            sys.exit("bench.py: --kv e4m3 needs a bf16 workload")
         x = wl.kv_to_e4m3(x)
     paged = args.page_size > 0
     active = None
@@ -129,6 +124,9 @@ def main():
     live_p = live_b.reshape(w.P, w.G).any(axis=1)
     ab = wl.algorithmic_bytes(w, np.where(live_p, x["prefix_lens"], 0), np.where(live_b, x["suffix_lens"], 0),
                               kv_elem_bytes=1 if kv8 else 0)
+    # what the K/V-streaming kernel itself has to read: the K/V rows, q and the lengths (out and lse are the
+    # combine kernel's; the partial results between the two kernels are scratch, not the method's bytes)
+    kern_bytes = ab["prefix"] + ab["suffix"] + w.B * w.Hq * w.d * w.elem_bytes + 4 * (w.P + w.B)
 
     def dev_t(a):
         if a.dtype == np.uint16:
@@ -167,58 +165,42 @@ def main():
         if rc != 0:
             raise B.RldaError(rc)
 
-    if args.copy_probe:                       # a plain copy of known size, for calibrating rocprofv3 byte counters
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
-
-    # what a plain device-to-device copy of 1 GiB moves on this machine (bytes read + bytes written per second):
-    # context for the published peak the roofline is priced against
-    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    b = torch.empty_like(a)
-    b.copy_(a)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(5):
-        b.copy_(a)
-    e1.record(stream)
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2 * float(1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
-    del a, b
-
-    for i in range(args.warmup):
+    for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
-
-    # three HIP events per step on the launch stream: before the call, after the K/V-streaming
-    # kernel (recorded by the library), after the call
-    ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(args.steps)]
-    for _, m, _ in ev:
-        m.record(stream)                      # materialise the handle the library records into
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    timed = [i for i in range(args.steps) if i % max(args.event_every, 1) == 0]
-    for i in range(args.steps):
-        if i % max(args.event_every, 1) == 0:
-            ev[i][0].record(stream)
-            step(i, ev[i][1].cuda_event)
-            ev[i][2].record(stream)
-        else:
-            step(i)
+    for i in range(steps):
+        step(i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    kern_ms = np.array([ev[i][0].elapsed_time(ev[i][1]) for i in timed])
-    rest_ms = np.array([ev[i][1].elapsed_time(ev[i][2]) for i in timed])
+    ms_per_step = (t1 - t0) * 1e3 / steps
     value = int(live_b.sum()) / (ms_per_step * 1e-3)    # one query token per live sequence and step
+
+    # per-call timings from HIP events on the launch stream: first the whole call (two events), then the
+    # K/V-streaming kernel alone (a third event, recorded by the library between its two kernels; recording
+    # it lengthens the step, so the whole-call figures come from the two-event loop)
+    n_ev = max(event_calls, 1)
+    ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for i, (a, b) in enumerate(ev2):
+        a.record(stream); step(i); b.record(stream)
+    torch.cuda.synchronize()
+    call_ms = [a.elapsed_time(b) for a, b in ev2]
+    ev3 = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(n_ev)]
+    for _, m, _ in ev3:
+        m.record(stream)                      # materialise the handle the library records into
+    torch.cuda.synchronize()
+    for i, (a, m, b) in enumerate(ev3):
+        a.record(stream); step(i, m.cuda_event); b.record(stream)
+    torch.cuda.synchronize()
+    kern_ms = [a.elapsed_time(m) for a, m, _ in ev3]
+    rest_ms = [m.elapsed_time(b) for _, m, b in ev3]
 
     # sanity: the timed configuration still matches the oracle on sampled rows
     rng = np.random.default_rng(0)
-    rows = np.stack([rng.integers(0, w.B, 64), rng.integers(0, w.Hq, 64)], 1).astype(np.int32)
+    n_rows = 64 if full else 24
+    rows = np.stack([rng.integers(0, w.B, n_rows), rng.integers(0, w.Hq, n_rows)], 1).astype(np.int32)
     from oracle import ref
+
     def oracle(**kw):
         if paged:
             return ref.decode_attn_paged_ref(x["q"], x["k_prefix"], x["v_prefix"], x["prefix_lens"], x["k_pages"],
@@ -237,6 +219,27 @@ def main():
     fin = [(b, h) for b, h in rows if np.isfinite(rl[b, h])]
     err_l = max([abs(float(l[b, h]) - rl[b, h]) for b, h in fin], default=0.0)
     parity_ok = bool(err_o <= tol_o and err_l <= tol_l)
+
+    kern = stats_us(kern_ms)
+    call = stats_us(call_ms)
+    gbps = lambda nbytes, us: nbytes / (us * 1e-6) / 1e9
+    res = {
+        "workload": w.name, "ms_per_step": ms_per_step, "value": value, "steps": steps, "plan": plan,
+        "algorithmic_bytes": ab, "kernel_algorithmic_bytes": kern_bytes,
+        "whole_step_GBps": gbps(ab["total"], ms_per_step * 1e3),
+        "whole_step_frac_of_hbm_peak": gbps(ab["total"], ms_per_step * 1e3) / HBM_PEAK_GBS,
+        "whole_call_us_by_events": call,
+        "kernel_us_by_events": kern,
+        "kernel_GBps": gbps(kern_bytes, kern["median"]),
+        "kernel_frac_of_hbm_peak": gbps(kern_bytes, kern["median"]) / HBM_PEAK_GBS,
+        "rest_of_call_us_median": float(np.median(rest_ms) * 1e3),
+        "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
+        "mean_prefix_len": float(x["prefix_lens"].mean()),
+        "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
+    }
+    if not full:
+        del sets, base, descs, ws
+        return res
 
     # CPU baseline: the oracle as it stands on a bounded sample (whole sequences, all heads)
     cpu = None
@@ -291,38 +294,133 @@ def main():
             dn.algo = keep
         naive = {"kernel": "simple_kernel", "ms_per_step": nms, "steps": args.naive_steps,
                  "GBps": ab["total"] / (nms * 1e-3) / 1e9}
+    res["cpu_baseline"] = cpu
+    res["naive_gpu_baseline"] = naive
+    res["config"] = {"workload": f"{w.name}: {w.note}; suffix {w.suffix}", "P": w.P, "G": w.G, "Hq": w.Hq,
+                     "Hkv": w.Hkv, "d": w.d, "algo": {1: "simple", 2: "shared"}.get(plan, str(plan)),
+                     "suffix_store": f"paged, {args.page_size} rows per page" if paged else "contiguous",
+                     "kv_store": "e4m3 bytes, one factor per KV head" if kv8 else w.dtype,
+                     "finished_sequences": int((~live_b).sum()),
+                     "kv_sets_rotated": len(sets),
+                     "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
+                     "mean_prefix_len": float(x["prefix_lens"].mean())}
+    res["dtype"] = w.dtype
+    res["traffic"] = None if paged or kv8 else measured_traffic(w.name, plan)
+    return res
 
-    kern_us = float(kern_ms.mean() * 1e3)
-    achieved = ab["total"] / (kern_us * 1e-6) / 1e9
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="vlm7b", help="tiny | vlm3b | vlm7b | agentic | highbatch")
+    ap.add_argument("--algo", default="auto", choices=["auto", "simple", "shared"])
+    ap.add_argument("--sets", type=int, default=3, help="rotating copies of the KV tensors")
+    ap.add_argument("--event-calls", type=int, default=120,
+                    help="calls timed one by one with HIP events (whatever --steps is), for the median / min / p90 figures")
+    ap.add_argument("--others", type=int, default=-1,
+                    help="1: also run the other four workloads in short form (key other_workloads); 0: do not; "
+                         "default: only when --workload is the default one")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three 1 GiB device-to-device copies (reference for scaling HBM counters)")
+    ap.add_argument("--kv", default="bf16", choices=["bf16", "e4m3"],
+                    help="element type of the K/V stores (e4m3: one byte per element plus a factor per KV head; "
+                         "q and the arithmetic stay bf16)")
+    ap.add_argument("--naive-steps", type=int, default=20,
+                    help="steps of the unoptimised GPU kernel timed as a reference row (0 = skip)")
+    ap.add_argument("--page-size", type=int, default=0,
+                    help="0: contiguous suffix store (the headline configuration); else rows per page of a paged store")
+    ap.add_argument("--finished", type=float, default=0.0,
+                    help="fraction of sequences marked finished (paged store only)")
+    ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
+    ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss", "prefill"],
+                    help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel; "
+                         "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens; "
+                         "prefill: causal attention of the workload's prompts over themselves")
+    ap.add_argument("--tokens", type=int, default=1024, help="policy_loss: token capacity per sequence")
+    ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
+    ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
+    ap.add_argument("--no-ref", action="store_true", help="token_logprob: no reference logits (no KL)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this is a single-GPU kernel library; only --gpus 1 is supported "
+              "(the path shards by prompt group with no exchange, nothing to measure across GPUs here)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_21450_amd import binding as B
+    from paper_2512_21450_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    if args.op == "token_logprob":
+        return bench_token_logprob(args, torch, B, wl, dev)
+    if args.op == "policy_loss":
+        return bench_policy_loss(args, torch, B, wl, dev)
+    if args.op == "prefill":
+        return bench_prefill(args, torch, B, wl, dev)
+    if args.kv == "e4m3" and wl.WORKLOADS[args.workload].dtype != "bf16":
+        sys.exit("bench.py: --kv e4m3 needs a bf16 workload")
+    stream = torch.cuda.current_stream()
+
+    if args.copy_probe:                       # a plain copy of known size, for calibrating rocprofv3 byte counters
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev).random_(0, 255)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+
+    ceiling = streaming_read_ceiling(torch, dev, stream)
+    r = run_decode(args, torch, B, wl, dev, args.workload, args.steps, args.warmup, args.event_calls, full=True)
+    others = None
+    default_run = args.workload == "vlm7b" and args.page_size == 0 and args.kv == "bf16" and args.algo == "auto"
+    if args.others == 1 or (args.others < 0 and default_run):
+        others = {}
+        for name in OTHER_WORKLOADS:
+            if name == args.workload:
+                continue
+            o = run_decode(args, torch, B, wl, dev, name, min(args.steps, 100), min(args.warmup, 10),
+                           min(args.event_calls, 60), full=False)
+            others[name] = {k: o[k] for k in ("ms_per_step", "value", "plan", "algorithmic_bytes", "whole_step_GBps",
+                                              "whole_step_frac_of_hbm_peak", "whole_call_us_by_events",
+                                              "kernel_us_by_events", "kernel_frac_of_hbm_peak", "mean_suffix_len",
+                                              "max_suffix_len", "mean_prefix_len", "parity")}
+            torch.cuda.empty_cache()
+
+    kern = r["kernel_us_by_events"]
+    achieved = r["kernel_GBps"]
     res = {
         "metric": "decode-attn query-tokens/sec and achieved HBM GB/s (% of MI355X peak), 7B shape",
-        "value": value, "unit": "query-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.note}; suffix {w.suffix}", "P": w.P, "G": w.G, "Hq": w.Hq,
-                   "Hkv": w.Hkv, "d": w.d, "algo": {1: "simple", 2: "shared"}.get(plan, str(plan)),
-                   "suffix_store": f"paged, {args.page_size} rows per page" if paged else "contiguous",
-                   "kv_store": "e4m3 bytes, one factor per KV head" if kv8 else w.dtype,
-                   "finished_sequences": int((~live_b).sum()),
-                   "kv_sets_rotated": len(sets),
-                   "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
-                   "mean_prefix_len": float(x["prefix_lens"].mean())},
-        "achieved_GBps_whole_step": ab["total"] / (ms_per_step * 1e-3) / 1e9,
-        "pct_of_hbm_peak_whole_step": 100.0 * ab["total"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "algorithmic_bytes": ab,
+        "value": r["value"], "unit": "query-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": r["dtype"], "data": "synthetic",
+        "config": r["config"],
+        "achieved_GBps_whole_step": r["whole_step_GBps"],
+        "pct_of_hbm_peak_whole_step": 100.0 * r["whole_step_frac_of_hbm_peak"],
+        "whole_call_us_by_events": r["whole_call_us_by_events"],
+        "algorithmic_bytes": r["algorithmic_bytes"],
+        # the dominant kernel alone: the bytes it has to read / its duration (median over the event-timed calls)
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None if paged or kv8 else measured_traffic(w.name, plan),
-                     "kernel": "partial_kernel" if plan == 2 else "simple_kernel",
-                     "kernel_us_mean": kern_us, "kernel_us_min": float(kern_ms.min() * 1e3),
-                     "kernel_us_p90": float(np.percentile(kern_ms, 90) * 1e3),
-                     "rest_of_step_us_mean": float(rest_ms.mean() * 1e3),
-                     "plain_copy_GBps_on_this_box": copy_gbps},
-        "cpu_baseline": cpu,
-        "naive_gpu_baseline": naive,
-        "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": r["traffic"],
+                     "traffic_source": "rocprofv3 counters of an earlier profile run of the same sources (profiles/)",
+                     "kernel": "partial_kernel" if r["plan"] == 2 else "simple_kernel",
+                     "kernel_algorithmic_bytes": r["kernel_algorithmic_bytes"],
+                     "kernel_us_median": kern["median"], "kernel_us_min": kern["min"], "kernel_us_p90": kern["p90"],
+                     "event_timed_calls": kern["n"],
+                     "rest_of_call_us_median": r["rest_of_call_us_median"],
+                     "streaming_read_ceiling_GBps": ceiling},
+        "cpu_baseline": r["cpu_baseline"],
+        "naive_gpu_baseline": r["naive_gpu_baseline"],
+        "parity": r["parity"],
+        "other_workloads": others,
     }
     print(json.dumps(res))
-    if not parity_ok:
+    ok = r["parity"]["ok"] and all(o["parity"]["ok"] for o in (others or {}).values())
+    if not ok:
         sys.exit(1)
 
 

@@ -12,6 +12,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librl_decode_attn.so")
+# measurement aid of bench.py (a loads-only streaming kernel), kept out of the product library
+PROBE_LIB = os.path.join(HERE, "libbench_stream_read.so")
+PROBE_SOURCES = ["bench_stream_read.hip"]
 SOURCES = ["rlda_api.hip", "rlda_simple.hip", "rlda_shared.hip", "rlda_token_logprob.hip", "rlda_kv_append.hip",
            "rlda_policy_loss.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
@@ -19,9 +22,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False) -> str:
+def _compile(out: str, sources, verbose: bool) -> None:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-o", LIB, *[os.path.join(CSRC, s) for s in SOURCES]]
+    cmd = [hipcc, *FLAGS, "-o", out, *[os.path.join(CSRC, s) for s in sources]]
     if verbose:
         print(" ".join(cmd))
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -31,6 +34,11 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError(f"hipcc failed:\n{err}")
     if verbose and err.strip():
         print(err, file=sys.stderr)
+
+
+def build(verbose: bool = False) -> str:
+    _compile(LIB, SOURCES, verbose)
+    _compile(PROBE_LIB, PROBE_SOURCES, verbose)
     return LIB
 
 
