@@ -176,3 +176,48 @@ def decode_attn_paged_ref(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages, 
         out[dead] = 0.0
         lse[dead] = -np.inf
     return out, lse
+
+
+def concat_levels(levels, B):
+    """Per-sequence key lists of a tree of shared segments, written out.
+
+    ``levels``: list of (k, v, lens, group): stores [n_seg, Hkv, cap, d], lengths [n_seg], and the number
+    of consecutive sequences that share one segment (n_seg * group == B): sequence b attends to segment
+    b // group of every level.  Returns (k_cat, v_cat, cat_lens): [B, Hkv, cap_total, d] stores that hold,
+    for each sequence, the live rows of its segment of level 0, then of level 1, ... one after the other
+    (lengths clamped to [0, cap]), and the number of rows per sequence.  Plain indexing, no arithmetic on
+    values.  With these as a "prefix" of its own per sequence (group size 1) the attention over a tree of
+    shared prefixes is, by definition, the attention over the concatenated keys.
+    """
+    assert len(levels) >= 1
+    k0 = levels[0][0]
+    Hkv, d = k0.shape[1], k0.shape[3]
+    cap_total = max(sum(int(k.shape[2]) for k, _, _, _ in levels), 1)
+    k_cat = np.zeros((B, Hkv, cap_total, d), dtype=k0.dtype)
+    v_cat = np.zeros((B, Hkv, cap_total, d), dtype=k0.dtype)
+    cat_lens = np.zeros(B, dtype=np.int32)
+    for b in range(B):
+        pos = 0
+        for k, v, lens, group in levels:
+            assert k.shape[0] * group == B and k.shape == v.shape
+            s = b // group
+            L = int(min(max(int(lens[s]), 0), k.shape[2]))
+            k_cat[b, :, pos:pos + L, :] = k[s, :, :L, :]
+            v_cat[b, :, pos:pos + L, :] = v[s, :, :L, :]
+            pos += L
+        cat_lens[b] = pos
+    return k_cat, v_cat, cat_lens
+
+
+def decode_attn_tree_ref(q, levels, k_suffix, v_suffix, suffix_lens, scale, rows=None, n_threads=0):
+    """Attention of every sequence over the segments it shares on each level of a prefix tree
+    (see concat_levels) followed by its own suffix: the two-pass fp64 attention over the concatenated keys."""
+    B = q.shape[0]
+    if not levels:
+        Hkv, d = k_suffix.shape[1], k_suffix.shape[3]
+        kc = np.zeros((B, Hkv, 1, d), dtype=k_suffix.dtype)
+        return decode_attn_ref(q, kc, kc, np.zeros(B, np.int32), k_suffix, v_suffix, suffix_lens, scale, 1,
+                               rows=rows, n_threads=n_threads)
+    k_cat, v_cat, cat_lens = concat_levels(levels, B)
+    return decode_attn_ref(q, k_cat, v_cat, cat_lens, k_suffix, v_suffix, suffix_lens, scale, 1,
+                           rows=rows, n_threads=n_threads)
