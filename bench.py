@@ -335,10 +335,12 @@ def main():
                     help="fraction of sequences marked finished (paged store only)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0, help="wall time given to the CPU-oracle leg")
     ap.add_argument("--cpu-seqs", type=int, default=256, help="sequences in the CPU-oracle sample (0 = skip)")
-    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss", "prefill"],
+    ap.add_argument("--op", default="decode_attn", choices=["decode_attn", "token_logprob", "policy_loss", "prefill", "tree"],
                     help="decode_attn: the headline path; token_logprob: per-token log-prob / entropy / KL kernel; "
                          "policy_loss: group advantages + clipped policy loss over --rows sequences of --tokens tokens; "
-                         "prefill: causal attention of the workload's prompts over themselves")
+                         "prefill: causal attention of the workload's prompts over themselves; "
+                         "tree: rl_decode_attn_tree on a two-level agentic batch, beside the same step composed of "
+                         "two rl_decode_attn calls and rl_lse_combine")
     ap.add_argument("--tokens", type=int, default=1024, help="policy_loss: token capacity per sequence")
     ap.add_argument("--rows", type=int, default=256, help="token_logprob: rows of logits (tokens)")
     ap.add_argument("--vocab", type=int, default=0, help="token_logprob: vocabulary size (default: Qwen2's 151936)")
@@ -362,6 +364,8 @@ def main():
         return bench_policy_loss(args, torch, B, wl, dev)
     if args.op == "prefill":
         return bench_prefill(args, torch, B, wl, dev)
+    if args.op == "tree":
+        return bench_tree(args, torch, B, wl, dev)
     if args.kv == "e4m3" and wl.WORKLOADS[args.workload].dtype != "bf16":
         sys.exit("bench.py: --kv e4m3 needs a bf16 workload")
     stream = torch.cuda.current_stream()
@@ -420,6 +424,124 @@ def main():
     }
     print(json.dumps(res))
     ok = r["parity"]["ok"] and all(o["parity"]["ok"] for o in (others or {}).values())
+    if not ok:
+        sys.exit(1)
+
+
+def bench_tree(args, torch, B, wl, dev):
+    """One step = one rl_decode_attn_tree call on a two-level agentic batch (7B shape, 16 prompts x G = 8: the
+    prompt shared by the 8 samples, a first turn shared by sub-groups of 4, long-tailed own suffixes), and the
+    same step composed of what existed before: one rl_decode_attn call per level and rl_lse_combine."""
+    Bn, Hq, Hkv, d, G0, G1 = 128, 28, 4, 128, 8, 4
+    x = wl.make_tree_inputs(1004, Bn, Hq, Hkv, d, [(G0, 1344, ("agentic", 3, 256, 64, 192)), (G1, 512, ("uniform", 512))],
+                            4096, ("lognormal", 300.0, 1.0), threads=16)
+    scale = 1.0 / np.sqrt(d)
+    to_dev = lambda a: (torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16) if a.dtype == np.uint16
+                        else torch.from_numpy(a).to(dev))
+    sets = []
+    for i in range(max(args.sets, 1)):
+        lv = [(to_dev(k), to_dev(v), to_dev(l), g) for k, v, l, g in x["levels"]]
+        sets.append(dict(q=to_dev(x["q"]), lv=lv, ks=to_dev(x["k_suffix"]), vs=to_dev(x["v_suffix"]), sl=to_dev(x["suffix_lens"])))
+    out = torch.empty((Bn, Hq, d), dtype=torch.float32, device=dev)
+    lse = torch.empty((Bn, Hq), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+    descs, ws = [], None
+    for t in sets:
+        ds = B.tree_desc_from_tensors(t["q"], t["lv"], t["ks"], t["vs"], t["sl"], scale, out, lse)
+        if ws is None:
+            ws = torch.empty(max(B.rl_decode_attn_tree_workspace_bytes(ds), 256), dtype=torch.uint8, device=dev)
+        ds.workspace, ds.workspace_bytes = ws.data_ptr(), ws.numel()
+        descs.append(ds)
+
+    def step_tree(i):
+        rc = B.rl_decode_attn_tree_raw(descs[i % len(descs)], sh)
+        if rc != 0:
+            raise B.RldaError(rc)
+
+    # the composition: level 0 as a prefix-only call, level 1 as the "prefix" of groups of G1 with the suffixes, then the merge
+    parts_o = torch.empty((2, Bn, Hq, d), dtype=torch.float32, device=dev)
+    parts_l = torch.empty((2, Bn, Hq), dtype=torch.float32, device=dev)
+    no_len = torch.zeros(Bn, dtype=torch.int32, device=dev)
+    comp, ws2 = [], None
+    for t in sets:
+        (k0, v0, l0, _), (k1, v1, l1, _) = t["lv"]
+        ks0 = t["ks"][:, :, :0].contiguous()
+        da = B.desc_from_tensors(t["q"], k0, v0, l0, ks0, ks0, no_len, scale, G0, parts_o[0], parts_l[0])
+        db = B.desc_from_tensors(t["q"], k1, v1, l1, t["ks"], t["vs"], t["sl"], scale, G1, parts_o[1], parts_l[1])
+        if ws2 is None:
+            n2 = max(B.rl_decode_attn_workspace_bytes(da), B.rl_decode_attn_workspace_bytes(db), 256)
+            ws2 = torch.empty(n2, dtype=torch.uint8, device=dev)
+        for dd in (da, db):
+            dd.workspace, dd.workspace_bytes = ws2.data_ptr(), ws2.numel()
+        comp.append((da, db))
+    out2 = torch.empty_like(out)
+    lse2 = torch.empty_like(lse)
+
+    def step_comp(i):
+        da, db = comp[i % len(comp)]
+        rc = B.rl_decode_attn_raw(da, sh) or B.rl_decode_attn_raw(db, sh)
+        if rc != 0:
+            raise B.RldaError(rc)
+        B.rl_lse_combine(parts_o.view(2, Bn * Hq, d), parts_l.view(2, Bn * Hq), out2.view(Bn * Hq, d), lse2.view(Bn * Hq))
+
+    def timed(step):
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3 / args.steps
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(max(args.event_calls, 1))]
+        for i, (a, b) in enumerate(ev):
+            a.record(stream); step(i); b.record(stream)
+        torch.cuda.synchronize()
+        return wall, stats_us([a.elapsed_time(b) for a, b in ev])
+
+    ms_tree, ev_tree = timed(step_tree)
+    ms_comp, ev_comp = timed(step_comp)
+    row = Hkv * 2 * d * 2
+    lens0, lens1 = x["levels"][0][2], x["levels"][1][2]
+    nbytes = (int(lens0.sum()) + int(lens1.sum()) + int(x["suffix_lens"].sum())) * row \
+        + Bn * Hq * d * 2 + Bn * Hq * d * 4 + Bn * Hq * 4 + 4 * (len(lens0) + len(lens1) + Bn)
+
+    from oracle import ref
+    rng = np.random.default_rng(0)
+    rows = np.stack([rng.integers(0, Bn, 48), rng.integers(0, Hq, 48)], 1).astype(np.int32)
+    c0 = time.perf_counter()
+    ro, rl = ref.decode_attn_tree_ref(x["q"], x["levels"], x["k_suffix"], x["v_suffix"], x["suffix_lens"], scale, rows=rows)
+    c1 = time.perf_counter()
+    step_tree(0); step_comp(0)
+    torch.cuda.synchronize()
+    errs = {}
+    for name, (o, l) in (("tree", (out, lse)), ("composition", (out2, lse2))):
+        o, l = o.cpu().numpy(), l.cpu().numpy()
+        errs[name] = (max(float(np.abs(o[b, h] - ro[b, h]).max()) for b, h in rows),
+                      max(abs(float(l[b, h]) - rl[b, h]) for b, h in rows))
+    ok = all(eo <= 1e-2 and el <= 1e-3 for eo, el in errs.values())
+    achieved = nbytes / (ms_tree * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "prefix-tree decode-attn query-tokens/sec and achieved HBM GB/s", "value": Bn / (ms_tree * 1e-3),
+        "unit": "query-tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_tree,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"two-level agentic batch: {Bn} sequences, {Hq}/{Hkv} heads, prompt shared by {G0} "
+                               f"(mean {lens0.mean():.0f} keys), first turn shared by {G1} (mean {lens1.mean():.0f}), own "
+                               f"suffix mean {x['suffix_lens'].mean():.0f} max {int(x['suffix_lens'].max())}",
+                   "kv_sets_rotated": len(sets)},
+        "algorithmic_bytes": nbytes,
+        "call_us_by_events": ev_tree,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "partial_kernel (tree form) + combine_kernel, whole call"},
+        "composition_of_existing_calls": {"what": "rl_decode_attn (level 0, no suffix) + rl_decode_attn (level 1 as prefix, with "
+                                                  "suffixes) + rl_lse_combine: five kernels, q read twice, fp32 partials through HBM",
+                                          "ms_per_step": ms_comp, "call_us_by_events": ev_comp,
+                                          "speedup_of_tree_call": ms_comp / ms_tree},
+        "cpu_baseline": {"value": len(rows) / Hq / (c1 - c0), "unit": "query-tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+                         "sample": f"{len(rows)} (sequence, head) rows of {Bn * Hq}, {c1 - c0:.2f} s"},
+        "parity": {"ok": bool(ok), "max_abs_err_out_lse": errs},
+    }))
     if not ok:
         sys.exit(1)
 

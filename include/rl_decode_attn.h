@@ -244,6 +244,67 @@ size_t rl_decode_attn_paged_workspace_bytes(const rlda_paged_desc* desc);
 int    rl_decode_attn_paged_plan(const rlda_paged_desc* desc);
 
 /*
+ * ---- A tree of shared prefixes ---------------------------------------------------
+ *
+ * The trajectories of a group share more than the prompt when the rollout has
+ * several turns: in the paper's agentic tasks (Sec. 5.1, tasks (4) and (5), and
+ * the multi-turn direction named as future work) a state is the prompt s_0
+ * followed by turns that themselves hold observations, and sub-groups of the K
+ * trajectories sampled from s_0 (Algorithm 1) may have a first turn in common.
+ * The keys of sequence b are then, level by level, the segment it shares with
+ * group_0 - 1 others, the segment it shares with group_1 - 1 others, ..., and
+ * finally its own suffix.  This call takes that list:
+ *
+ *   level l:  k, v   [B / group_l, Hkv, cap_l, d]   one segment per `group_l`
+ *                                                    consecutive sequences
+ *             lens   [B / group_l]                   valid rows, clamped to [0, cap_l]
+ *   sequence b attends to segment b / group_l of every level and to its suffix.
+ *
+ * The result is the attention of the header comment over the union of these
+ * keys (rl_decode_attn is the case of one level with group_0 = G).  Every
+ * segment is read from HBM once for all the sequences and query heads that
+ * share it; one launch of the K/V-streaming kernel walks all levels and the
+ * suffixes, one combine launch merges the partial results; q is read once.
+ *
+ * group_l >= 1 must divide B; levels need not nest.  0 <= n_levels <=
+ * RLDA_MAX_TREE_LEVELS.  Supported: RLDA_BF16, d = 128, Hq/Hkv <= 16,
+ * max_l(group_l) * Hq/Hkv <= 64, scale > 0, contiguous stores; anything else
+ * returns RLDA_ERR_UNSUPPORTED (compose rl_decode_attn calls and rl_lse_combine
+ * instead).  Other fields, ownership, stream, clamping and error behaviour as
+ * for rlda_desc / rl_decode_attn.
+ */
+#define RLDA_MAX_TREE_LEVELS 4
+typedef struct {
+  const void*    k;            /* [B / group, Hkv, cap, d]  (may be NULL if cap == 0)            */
+  const void*    v;            /* same shape                                                     */
+  const int32_t* lens;         /* [B / group]                                                    */
+  int32_t        group;        /* consecutive sequences that share one segment                   */
+  int32_t        cap;          /* row capacity of the level's segments (>= 0)                    */
+} rlda_tree_level;
+
+typedef struct {
+  uint32_t struct_size;        /* = sizeof(rlda_tree_desc)                                       */
+  int32_t  dtype;              /* RLDA_BF16                                                      */
+  int32_t  B;                  /* sequences                                                      */
+  int32_t  Hq, Hkv, d;
+  int32_t  n_levels;           /* shared levels in use                                           */
+  int32_t  Ls_cap;             /* row capacity of the suffix buffers                             */
+  float    scale;
+  rlda_tree_level levels[RLDA_MAX_TREE_LEVELS];
+  const void*    q;            /* [B, Hq, d]                                                     */
+  const void*    k_suffix;     /* [B, Hkv, Ls_cap, d]                                            */
+  const void*    v_suffix;
+  const int32_t* suffix_lens;  /* [B]                                                            */
+  float*   out;                /* [B, Hq, d] fp32                                                */
+  float*   lse;                /* [B, Hq] fp32; may be NULL                                      */
+  void*    workspace;
+  size_t   workspace_bytes;    /* >= rl_decode_attn_tree_workspace_bytes                         */
+} rlda_tree_desc;
+
+int    rl_decode_attn_tree(const rlda_tree_desc* desc, void* hip_stream);
+size_t rl_decode_attn_tree_workspace_bytes(const rlda_tree_desc* desc);   /* 0 if invalid or unsupported */
+
+/*
  * The log-sum-exp combine step on its own (merge of split-softmax partials):
  * for each of n_rows rows, given n_parts partial results over disjoint key
  * sets, o_parts [n_parts, n_rows, d] fp32 (each already normalised) and

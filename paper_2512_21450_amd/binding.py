@@ -70,7 +70,37 @@ class rlda_paged_desc(ctypes.Structure):
     ]
 
 
+RLDA_MAX_TREE_LEVELS = 4
+
+
+class rlda_tree_level(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("lens", ctypes.c_void_p),
+                ("group", ctypes.c_int32), ("cap", ctypes.c_int32)]
+
+
+class rlda_tree_desc(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_uint32),
+        ("dtype", ctypes.c_int32),
+        ("B", ctypes.c_int32),
+        ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("n_levels", ctypes.c_int32),
+        ("Ls_cap", ctypes.c_int32),
+        ("scale", ctypes.c_float),
+        ("levels", rlda_tree_level * RLDA_MAX_TREE_LEVELS),
+        ("q", ctypes.c_void_p),
+        ("k_suffix", ctypes.c_void_p), ("v_suffix", ctypes.c_void_p), ("suffix_lens", ctypes.c_void_p),
+        ("out", ctypes.c_void_p), ("lse", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
 _dp = ctypes.POINTER(rlda_desc)
+_tp = ctypes.POINTER(rlda_tree_desc)
+_lib.rl_decode_attn_tree.restype = ctypes.c_int
+_lib.rl_decode_attn_tree.argtypes = [_tp, ctypes.c_void_p]
+_lib.rl_decode_attn_tree_workspace_bytes.restype = ctypes.c_size_t
+_lib.rl_decode_attn_tree_workspace_bytes.argtypes = [_tp]
 _pp = ctypes.POINTER(rlda_paged_desc)
 _lib.rl_decode_attn_paged.restype = ctypes.c_int
 _lib.rl_decode_attn_paged.argtypes = [_pp, ctypes.c_void_p, ctypes.c_void_p]
@@ -187,6 +217,46 @@ def _kv_dtype_code(q, stores, k_scale, v_scale):
     return code
 
 
+def _check_lens(t, n, name, like):
+    """A length array as the kernels read it: int32, n entries, contiguous, on q's device."""
+    import torch
+    if t.dtype != torch.int32:
+        raise TypeError(f"{name} must be int32 (got {t.dtype}): the kernels read 4-byte lengths")
+    if t.numel() != n or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous array of {n} lengths (got shape {tuple(t.shape)})")
+    if t.device != like.device:
+        raise ValueError(f"{name} is on {t.device}, q on {like.device}")
+
+
+def _check_outputs(q, out, lse):
+    """out [B, Hq, d] and lse [B, Hq] (optional) as the kernels write them: float32, contiguous, on q's device."""
+    import torch
+    B, Hq, d = q.shape
+    for t, shape, name in ((out, (B, Hq, d), "out"), (lse, (B, Hq), "lse")):
+        if t is None:
+            if name == "out":
+                raise ValueError("out is required")
+            continue
+        if t.dtype != torch.float32:
+            raise TypeError(f"{name} must be float32 (got {t.dtype})")
+        if tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous tensor of shape {shape} (got {tuple(t.shape)})")
+        if t.device != q.device:
+            raise ValueError(f"{name} is on {t.device}, q on {q.device}")
+
+
+def _check_stores(q, pairs):
+    """every (K store, V store) pair: equal shapes, contiguous, on q's device"""
+    for k, v, name in pairs:
+        if k.shape != v.shape:
+            raise ValueError(f"v_{name} has shape {tuple(v.shape)}, k_{name} {tuple(k.shape)}")
+        for t in (k, v):
+            if not t.is_contiguous():
+                raise ValueError("tensors must be contiguous")
+            if t.device != q.device:
+                raise ValueError(f"a {name} store is on {t.device}, q on {q.device}")
+
+
 def desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, suffix_lens, scale, G,
                       out, lse=None, workspace=None, algo=RLDA_ALGO_AUTO, k_scale=None, v_scale=None) -> rlda_desc:
     """Descriptor over torch device tensors (shapes as in the header)."""
@@ -195,9 +265,12 @@ def desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix, su
     Ls_cap = k_suffix.shape[2]
     if B != P * G or k_suffix.shape[0] != B or k_suffix.shape[1] != Hkv:
         raise ValueError("inconsistent shapes")
-    for t in (q, k_prefix, v_prefix, k_suffix, v_suffix, prefix_lens, suffix_lens, out):
-        if not t.is_contiguous():
-            raise ValueError("tensors must be contiguous")
+    if not q.is_contiguous():
+        raise ValueError("tensors must be contiguous")
+    _check_stores(q, ((k_prefix, v_prefix, "prefix"), (k_suffix, v_suffix, "suffix")))
+    _check_lens(prefix_lens, P, "prefix_lens", q)
+    _check_lens(suffix_lens, B, "suffix_lens", q)
+    _check_outputs(q, out, lse)
     code = _kv_dtype_code(q, (k_prefix, v_prefix, k_suffix, v_suffix), k_scale, v_scale)
     ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
     return make_desc(code, P, G, Hq, Hkv, d, Lp_cap, Ls_cap, float(scale), algo,
@@ -252,6 +325,79 @@ def rl_decode_attn_static(q, k_prefix, v_prefix, prefix_lens, k_suffix, v_suffix
     return out, lse
 
 
+def make_tree_desc(dtype, B, Hq, Hkv, d, Ls_cap, scale, levels=(), **ptrs) -> rlda_tree_desc:
+    """Fill a tree descriptor from plain integers; ``levels``: (k_ptr, v_ptr, lens_ptr, group, cap) per level."""
+    ds = rlda_tree_desc()
+    ds.struct_size = ctypes.sizeof(rlda_tree_desc)
+    ds.dtype, ds.B, ds.Hq, ds.Hkv, ds.d, ds.Ls_cap, ds.scale = dtype, B, Hq, Hkv, d, Ls_cap, scale
+    ds.n_levels = len(levels)
+    for i, (k, v, lens, group, cap) in enumerate(levels[:RLDA_MAX_TREE_LEVELS]):
+        ds.levels[i].k, ds.levels[i].v, ds.levels[i].lens = k, v, lens
+        ds.levels[i].group, ds.levels[i].cap = group, cap
+    for k, v in ptrs.items():
+        setattr(ds, k, v)
+    return ds
+
+
+def rl_decode_attn_tree_workspace_bytes(desc: rlda_tree_desc) -> int:
+    return _lib.rl_decode_attn_tree_workspace_bytes(ctypes.byref(desc))
+
+
+def rl_decode_attn_tree_raw(desc: rlda_tree_desc, stream_handle=None) -> int:
+    """Direct call; returns the C return code."""
+    return _lib.rl_decode_attn_tree(ctypes.byref(desc), stream_handle)
+
+
+def tree_desc_from_tensors(q, levels, k_suffix, v_suffix, suffix_lens, scale, out, lse=None, workspace=None) -> rlda_tree_desc:
+    """Tree descriptor over torch device tensors.  ``levels``: list of (k [n_seg, Hkv, cap, d], v, lens [n_seg],
+    group) with n_seg * group == B."""
+    B, Hq, d = q.shape
+    Hkv, Ls_cap = k_suffix.shape[1], k_suffix.shape[2]
+    if len(levels) > RLDA_MAX_TREE_LEVELS:
+        raise ValueError(f"at most {RLDA_MAX_TREE_LEVELS} shared levels")
+    if k_suffix.shape[0] != B or not q.is_contiguous():
+        raise ValueError("inconsistent shapes")
+    pairs = [(k_suffix, v_suffix, "suffix")]
+    lv = []
+    ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
+    for i, (k, v, lens, group) in enumerate(levels):
+        if group < 1 or B % group or k.shape[0] * group != B or k.shape[1] != Hkv or k.shape[3] != d:
+            raise ValueError(f"level {i}: {tuple(k.shape)} stores with groups of {group} do not cover {B} sequences")
+        pairs.append((k, v, f"level {i}"))
+        _check_lens(lens, B // group, f"lens of level {i}", q)
+        lv.append((ptr(k), ptr(v), ptr(lens), int(group), int(k.shape[2])))
+    _check_stores(q, pairs)
+    _check_lens(suffix_lens, B, "suffix_lens", q)
+    _check_outputs(q, out, lse)
+    code = _kv_dtype_code(q, [t for k, v, _ in pairs for t in (k, v)], None, None)
+    return make_tree_desc(code, B, Hq, Hkv, d, Ls_cap, float(scale), lv, q=ptr(q), k_suffix=ptr(k_suffix),
+                          v_suffix=ptr(v_suffix), suffix_lens=ptr(suffix_lens), out=ptr(out), lse=ptr(lse),
+                          workspace=ptr(workspace),
+                          workspace_bytes=0 if workspace is None else workspace.numel() * workspace.element_size())
+
+
+def rl_decode_attn_tree(q, levels, k_suffix, v_suffix, suffix_lens, scale, out=None, lse=None, workspace=None, stream=None):
+    """One decode step over a tree of shared prefix segments plus the own suffixes; returns (out, lse)."""
+    import torch
+    if not q.is_cuda:
+        raise RuntimeError("rl_decode_attn_tree needs device tensors; there is no CPU path")
+    B, Hq, d = q.shape
+    if out is None:
+        out = torch.empty((B, Hq, d), dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device)
+    ds = tree_desc_from_tensors(q, levels, k_suffix, v_suffix, suffix_lens, scale, out, lse, workspace)
+    if workspace is None:
+        need = rl_decode_attn_tree_workspace_bytes(ds)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        ds.workspace, ds.workspace_bytes = workspace.data_ptr(), workspace.numel()
+    s = stream if stream is not None else torch.cuda.current_stream(q.device)
+    rc = _lib.rl_decode_attn_tree(ctypes.byref(ds), ctypes.c_void_p(s.cuda_stream))
+    if rc != RLDA_OK:
+        raise RldaError(rc)
+    return out, lse
+
+
 def make_paged_desc(dtype, P, G, Hq, Hkv, d, Lp_cap, page_size, max_pages, n_pages, scale,
                     algo=RLDA_ALGO_AUTO, **ptrs) -> rlda_paged_desc:
     """Fill a paged descriptor from plain integers; pointer fields default to NULL."""
@@ -291,9 +437,15 @@ def paged_desc_from_tensors(q, k_prefix, v_prefix, prefix_lens, k_pages, v_pages
         raise ValueError("inconsistent shapes")
     if block_table.dtype != torch.int32 or (seq_active is not None and seq_active.dtype != torch.uint8):
         raise TypeError("block_table must be int32 and seq_active uint8")
-    for t in (q, k_prefix, v_prefix, k_pages, v_pages, prefix_lens, suffix_lens, block_table, out):
+    if seq_active is not None and (seq_active.numel() != B or not seq_active.is_contiguous()):
+        raise ValueError(f"seq_active must hold one byte per sequence ({B})")
+    for t in (q, block_table):
         if not t.is_contiguous():
             raise ValueError("tensors must be contiguous")
+    _check_stores(q, ((k_prefix, v_prefix, "prefix"), (k_pages, v_pages, "pages")))
+    _check_lens(prefix_lens, P, "prefix_lens", q)
+    _check_lens(suffix_lens, B, "suffix_lens", q)
+    _check_outputs(q, out, lse)
     code = _kv_dtype_code(q, (k_prefix, v_prefix, k_pages, v_pages), k_scale, v_scale)
     ptr = lambda t: None if t is None or t.numel() == 0 else t.data_ptr()
     return make_paged_desc(code, P, G, Hq, Hkv, d, Lp_cap, page_size, block_table.shape[1], n_pages, float(scale),

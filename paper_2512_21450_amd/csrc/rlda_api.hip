@@ -12,6 +12,8 @@ namespace {
 
 using rlda::Problem;
 
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
 // Descriptor -> Problem.  Returns RLDA_OK or the error the descriptor itself shows.
 int to_problem(const rlda_desc* ds, Problem& pb) {
   if (!ds) return RLDA_ERR_INVALID;
@@ -84,7 +86,55 @@ size_t workspace_of(const Desc* desc) {
   return plan(pb) == RLDA_ALGO_SHARED ? rlda::shared_workspace_bytes(pb) : 0;
 }
 
-thread_local hipError_t g_last_hip_error = hipSuccess;
+// Tree descriptor -> Problem.  Returns RLDA_OK or the error the descriptor itself shows.
+int to_problem(const rlda_tree_desc* ds, Problem& pb) {
+  if (!ds) return RLDA_ERR_INVALID;
+  if (ds->struct_size != sizeof(rlda_tree_desc)) return RLDA_ERR_STRUCT_SIZE;
+  if (ds->B < 0 || ds->Hq <= 0 || ds->Hkv <= 0 || ds->d <= 0 || ds->Ls_cap < 0) return RLDA_ERR_INVALID;
+  if (ds->n_levels < 0 || ds->n_levels > RLDA_MAX_TREE_LEVELS) return RLDA_ERR_INVALID;
+  pb = Problem{};
+  pb.dtype = ds->dtype; pb.algo = RLDA_ALGO_SHARED;
+  pb.P = 0; pb.G = 1; pb.Hq = ds->Hq; pb.Hkv = ds->Hkv; pb.d = ds->d;
+  pb.Lp_cap = 0; pb.Ls_cap = ds->Ls_cap; pb.scale = ds->scale;
+  pb.q = ds->q; pb.k_suffix = ds->k_suffix; pb.v_suffix = ds->v_suffix; pb.suffix_lens = ds->suffix_lens;
+  pb.out = ds->out; pb.lse = ds->lse; pb.workspace = ds->workspace; pb.workspace_bytes = ds->workspace_bytes;
+  pb.tree_B = ds->B;
+  pb.n_levels = ds->n_levels;
+  for (int l = 0; l < ds->n_levels; ++l) {
+    const rlda_tree_level& lv = ds->levels[l];
+    if (lv.group < 1 || lv.cap < 0 || ds->B % lv.group != 0) return RLDA_ERR_INVALID;
+    pb.levels[l] = Problem::Level{lv.k, lv.v, lv.lens, ds->B / lv.group, lv.group, lv.cap};
+  }
+  return RLDA_OK;
+}
+
+// what the tree form runs on, or the reason it cannot
+int check_tree(const Problem& pb) {
+  if (pb.dtype != RLDA_F32 && pb.dtype != RLDA_BF16 && pb.dtype != RLDA_BF16_KV8) return RLDA_ERR_UNSUPPORTED;
+  if (pb.Hq % pb.Hkv != 0) return RLDA_ERR_UNSUPPORTED;
+  if ((int64_t)pb.tree_B * pb.Hq > (int64_t)1 << 30) return RLDA_ERR_UNSUPPORTED;
+  if (pb.n_levels == 0 || !rlda::shared_supported(pb)) return RLDA_ERR_UNSUPPORTED;   // no level: rl_decode_attn with P = B covers it
+  return RLDA_OK;
+}
+
+int enqueue_tree(const rlda_tree_desc* desc, void* hip_stream) {
+  Problem pb;
+  int rc = to_problem(desc, pb);
+  if (rc != RLDA_OK) return rc;
+  rc = check_tree(pb);
+  if (rc != RLDA_OK) return rc;
+  if (pb.tree_B == 0) return RLDA_OK;
+  if (!pb.q || !pb.suffix_lens || !pb.out) return RLDA_ERR_INVALID;
+  if (pb.Ls_cap > 0 && (!pb.k_suffix || !pb.v_suffix)) return RLDA_ERR_INVALID;
+  for (int l = 0; l < pb.n_levels; ++l)
+    if (!pb.levels[l].lens || (pb.levels[l].cap > 0 && (!pb.levels[l].k || !pb.levels[l].v))) return RLDA_ERR_INVALID;
+  const size_t need = rlda::shared_workspace_bytes(pb);
+  if (!pb.workspace || pb.workspace_bytes < need) return RLDA_ERR_WORKSPACE;
+  if (reinterpret_cast<uintptr_t>(pb.workspace) & 255u) return RLDA_ERR_WORKSPACE;
+  const hipError_t e = rlda::launch_shared(pb, static_cast<hipStream_t>(hip_stream), nullptr);
+  g_last_hip_error = e;
+  return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
+}
 
 // the tensors a non-empty batch needs
 int check_pointers(const Problem& pb) {
@@ -203,6 +253,13 @@ int rl_decode_attn_profiled(const rlda_desc* desc, void* hip_stream, void* mid_e
 
 int rl_decode_attn_static(const rlda_desc* desc, void* hip_stream) { return enqueue_static(desc, hip_stream); }
 size_t rl_decode_attn_static_workspace_limit(void) { return RLDA_STATIC_WORKSPACE_BYTES; }
+
+int rl_decode_attn_tree(const rlda_tree_desc* desc, void* hip_stream) { return enqueue_tree(desc, hip_stream); }
+size_t rl_decode_attn_tree_workspace_bytes(const rlda_tree_desc* desc) {
+  Problem pb;
+  if (to_problem(desc, pb) != RLDA_OK || check_tree(pb) != RLDA_OK) return 0;
+  return rlda::shared_workspace_bytes(pb);
+}
 
 int rl_decode_attn_paged_plan(const rlda_paged_desc* desc) { return plan_of(desc); }
 size_t rl_decode_attn_paged_workspace_bytes(const rlda_paged_desc* desc) { return workspace_of(desc); }

@@ -28,7 +28,28 @@ struct Problem {
   float* out; float* lse;
   void* workspace; size_t workspace_bytes;
   const float* k_scale; const float* v_scale;   // per-KV-head factors of an e4m3 K/V store, or null
+  // tree form (rl_decode_attn_tree): n_levels > 0 levels of shared segments in place of k_prefix / v_prefix /
+  // prefix_lens / P / G / Lp_cap; level l has n_seg segments of `cap` rows, each shared by `group` consecutive
+  // sequences (n_seg * group == tree_B)
+  int n_levels;
+  struct Level { const void* k; const void* v; const int32_t* lens; int n_seg, group, cap; } levels[RLDA_MAX_TREE_LEVELS];
+  int tree_B;
 };
+
+// sequences, entries of the prefix line (prompts, or the segments of all tree levels), largest sharing group
+inline int64_t n_sequences(const Problem& p) { return p.n_levels > 0 ? p.tree_B : (int64_t)p.P * p.G; }
+inline int64_t n_prefix_entries(const Problem& p) {
+  if (p.n_levels == 0) return p.P;
+  int64_t n = 0;
+  for (int l = 0; l < p.n_levels; ++l) n += p.levels[l].n_seg;
+  return n;
+}
+inline int max_group(const Problem& p) {
+  if (p.n_levels == 0) return p.G;
+  int g = 1;
+  for (int l = 0; l < p.n_levels; ++l) g = p.levels[l].group > g ? p.levels[l].group : g;
+  return g;
+}
 
 // bytes per stored K/V element
 inline int kv_elem_bytes(int dtype) { return dtype == RLDA_F32 ? 4 : (dtype == RLDA_BF16_KV8 ? 1 : 2); }

@@ -53,6 +53,12 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// One level of a tree of shared prefix segments (rl_decode_attn_tree): `n` segments, each shared by G
+// consecutive sequences (R = G * Hq/Hkv query rows per KV head); the level's segments are entries
+// first .. first + n - 1 of the prefix line.
+struct TreeLevel { const char* k; const char* v; const int32_t* lens; int first, G, R, cap; };
+constexpr int MAX_LEVELS = RLDA_MAX_TREE_LEVELS;   // 4
+
 struct SharedParams {
   const char* q; const char* kp; const char* vp; const char* ks; const char* vs;
   const int32_t* plens; const int32_t* slens;
@@ -75,12 +81,29 @@ struct SharedParams {
   int page_shift, max_pages, n_pages;
   // e4m3 K/V stores only (kernels instantiated with F8 = true): per-KV-head factors, or null
   const float* kscale; const float* vscale;
+  // tree form only (kernels instantiated with TREE = true): the prefix line holds the segments of all levels,
+  // level after level, P is their total number, G and R are the largest group's, kp / vp / plens are unused
+  TreeLevel lev[MAX_LEVELS];
+  int n_lev;
 };
+
+// the level that entry `e` of the prefix line belongs to (e is wavefront-uniform: scalar selects)
+__device__ __forceinline__ TreeLevel level_of(const SharedParams& P, int e) {
+  TreeLevel r = P.lev[0];
+#pragma unroll
+  for (int i = 1; i < MAX_LEVELS; ++i)
+    if (i < P.n_lev && e >= P.lev[i].first) r = P.lev[i];
+  return r;
+}
 
 // Effective lengths: clamped to the capacity; in the extended form a finished sequence has no
 // suffix, and a prompt none of whose G sequences is live has no prefix.
-template <bool EXT>
+template <bool EXT, bool TREE = false>
 __device__ __forceinline__ int plen_of(const SharedParams& P, int p) {
+  if constexpr (TREE) {
+    const TreeLevel lv = level_of(P, p);
+    return clampi(lv.lens[p - lv.first], 0, lv.cap);
+  }
   int L = clampi(P.plens[p], 0, P.Lp_cap);
   if (EXT && P.active) {
     bool any = false;
@@ -472,9 +495,11 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, in
 // memory pipeline and the matrix pipeline of the CU overlap and no bubble opens at a unit
 // boundary.  When a unit's run ends, the WG_WAVES / NRB wavefronts that share a row block are
 // merged through LDS and the partial is written.
-template <int NRB, int NT, bool EXT, bool F8, bool REREAD>
+// TREE: the units are segments of several levels, each with its own store, capacity and group size.
+struct PrefixUnit { const char* k; const char* v; int cap, R, b0; };   // stores of the segment (all KV heads), rows, first sequence
+template <int NRB, int NT, bool EXT, bool F8, bool REREAD, bool TREE>
 __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int tid) {
-  auto len_of = [&](int p) { return plen_of<EXT>(P, p); };
+  auto len_of = [&](int p) { return plen_of<EXT, TREE>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   using St = Stage<F8>;
   constexpr int NL = St::NL, GROWB = St::GROWB;
@@ -484,6 +509,17 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int lrow = St::lrow(lane), chunk = St::chunk(lane);
   auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
   auto head_of = [&](const Cur& c) { return c.j >> P.NHs; };
+  // where the K and V rows of unit c start in their store, its query rows and its first sequence
+  auto unit_of = [&](const Cur& c) {
+    if constexpr (TREE) {
+      const TreeLevel lv = level_of(P, c.u);
+      const size_t off = (size_t)((c.u - lv.first) * P.Hkv + head_of(c)) * lv.cap * GROWB;
+      return PrefixUnit{lv.k + off, lv.v + off, lv.cap, lv.R, (c.u - lv.first) * lv.G};
+    } else {
+      const size_t off = (size_t)(c.u * P.Hkv + head_of(c)) * P.Lp_cap * GROWB;
+      return PrefixUnit{P.kp + off, P.vp + off, P.Lp_cap, P.R, c.u * P.G};
+    }
+  };
   constexpr bool reread = REREAD;                           // every prefix tile is read once per row part: keep it cached
   char* mine = lds + wv * STAGE_B;
 
@@ -493,11 +529,13 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   WaveState<NT> st;
   float cu = P.c;                                           // score factor of the current unit
   auto issue_q = [&](const Cur& c) {                        // row = sample * r + head-in-group
+    int R = P.R, b0 = c.u * P.G;
+    if constexpr (TREE) { const PrefixUnit pu = unit_of(c); R = pu.R; b0 = pu.b0; }
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
       const int row = 64 * half_of(c) + rowbase + 16 * nt + m16;
-      const bool ok = row < P.R;
-      const int b = c.u * P.G + (ok ? row / P.r : 0), h = head_of(c) * P.r + (ok ? row % P.r : 0);
+      const bool ok = row < R;
+      const int b = b0 + (ok ? row / P.r : 0), h = head_of(c) * P.r + (ok ? row % P.r : 0);
       const char* qp = P.q + ((size_t)b * P.Hq + h) * ROWB + 16 * g;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
@@ -511,8 +549,9 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   int rem = n, gs = group_size(cur, rem);
   if (QPRE) issue_q(cur);
   if (wv < gs) {
-    const char* kb = P.kp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * GROWB;
-    const char* vb = P.vp + (size_t)(cur.u * P.Hkv + head_of(cur)) * P.Lp_cap * GROWB;
+    const PrefixUnit pu = unit_of(cur);
+    const char* kb = pu.k;
+    const char* vb = pu.v;
     const int key0 = (cur.t + wv) * TK, last = min(TK, cur.L - key0) - 1;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
@@ -523,7 +562,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   }
   bool fresh = true;
   while (rem > 0) {
-    const bool active = 64 * half_of(cur) + rowbase < P.R;  // this wavefront's row block exists in the unit's half
+    const bool active = 64 * half_of(cur) + rowbase < (TREE ? unit_of(cur).R : P.R);   // this wavefront's row block exists in the unit's half
     wait_vmem();
     if (wv < gs) stage_store<F8>(mine, mine + TILE_B, rk, rv, lrow, chunk);
     if (fresh) {
@@ -551,8 +590,9 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
     lds_barrier();
     if (QPRE && next_fresh) issue_q(nxt);
     const bool more = wv < ngs;                             // this wavefront fetches a tile of the next group
-    const char* kb = P.kp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * GROWB;
-    const char* vb = P.vp + (size_t)(nxt.u * P.Hkv + head_of(nxt)) * P.Lp_cap * GROWB;
+    const PrefixUnit pn = unit_of(nxt);
+    const char* kb = pn.k;
+    const char* vb = pn.v;
     const int key0 = (nxt.t + wv) * TK, last = min(TK, nxt.L - key0) - 1;
     // the upper half of the wavefronts issues a slice before each tile computation, the lower half
     // after it, so that they alternate between the memory pipeline and the matrix pipeline
@@ -707,7 +747,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   }
 }
 
-template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false>   // REREAD: KV groups of several row parts (NRB = 4)
+template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false, bool TREE = false>   // REREAD: KV groups of several row parts (NRB = 4)
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -723,7 +763,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
     int sum = 0;
     for (int i = c0; i < c1; ++i) {
       int e = 0;
-      if (i < P.P) e = ceil_div(plen_of<EXT>(P, i), TK);
+      if (i < P.P) e = ceil_div(plen_of<EXT, TREE>(P, i), TK);
       else if (i < P.P + P.B) e = ceil_div(slen_of<EXT>(P, i - P.P), TK);
       X[i] = e;                                             // read back below by this thread only
       sum += e;
@@ -762,8 +802,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   // each wavefront in its own stage of the LDS
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
-    cur_load(c, [&](int p) { return plen_of<EXT>(P, p); });
-    prefix_stream<NRB, NT, EXT, F8, REREAD>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
+    cur_load(c, [&](int p) { return plen_of<EXT, TREE>(P, p); });
+    prefix_stream<NRB, NT, EXT, F8, REREAD, TREE>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
@@ -780,7 +820,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
 // ---- combine: 32 lanes per (sequence, head) row.  Lane k of the row first owns part k: all lse
 // values of the row and the first eight parts' values are requested in one round trip; the lse
 // values become weights with two 32-lane reductions; then every lane accumulates its 4 columns.  Parts are taken in line order, so the sum has one fixed order.
-template <bool EXT>
+template <bool EXT, bool TREE = false>
 __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int row = blockIdx.x * 8 + (threadIdx.x >> 5);
   const int sub = threadIdx.x & 31, c4 = sub * 4;
@@ -805,10 +845,23 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   for (int base = 0;; base += 32) {
     // part `base + sub` of this row, as 2 * (row index in its partial array) + [suffix]
     int n = 0, mine = -1;
-    for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
-      if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
-      ++n;
-    });
+    if constexpr (TREE) {                                   // the row's segment on every level, in level order
+#pragma unroll
+      for (int l = 0; l < MAX_LEVELS; ++l) {
+        if (l < P.n_lev) {
+          const int e = P.lev[l].first + b / P.lev[l].G, erow = (b % P.lev[l].G) * P.r + hi_;
+          for_each_prefix_part(sc, X, P.Hkv, e, j, [&](int c) {
+            if (n == base + sub) mine = 2 * ((e * P.Hkv + j + c) * P.RS + erow);
+            ++n;
+          });
+        }
+      }
+    } else {
+      for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
+        if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
+        ++n;
+      });
+    }
     for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
       if (n == base + sub) mine = 2 * ((b * P.Hkv + j + WG_WAVES * rank + v) * P.r + hi_) + 1;
       ++n;
@@ -1307,12 +1360,12 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 struct Layout { size_t cum, pl, po, sl, so, total; };
 
 Layout layout(const Problem& ds) {
-  const size_t B = (size_t)ds.P * ds.G, r = ds.Hq / ds.Hkv, Rg = r * ds.G;
+  const size_t B = (size_t)n_sequences(ds), E = (size_t)n_prefix_entries(ds), r = ds.Hq / ds.Hkv, Rg = r * max_group(ds);
   const size_t NH = row_parts((int)Rg), R = NH > 1 ? 64 : Rg;   // rows per prefix partial slot
-  const size_t nps = (size_t)ds.P * ds.Hkv * NH + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
+  const size_t nps = E * ds.Hkv * NH + N_WG, nss = B * ds.Hkv + (size_t)WG_WAVES * N_WG;
   Layout L;
   size_t o = 0;
-  L.cum = o; o = align256(o + (ds.P + B + 1) * 4);
+  L.cum = o; o = align256(o + (E + B + 1) * 4);
   L.pl = o;  o = align256(o + nps * R * 2 * 4);
   L.po = o;  o = align256(o + nps * R * D * 2);
   L.sl = o;  o = align256(o + nss * r * 2 * 4);
@@ -1326,13 +1379,23 @@ Layout layout(const Problem& ds) {
 bool shared_supported(const Problem& ds) {
   if ((ds.dtype != RLDA_BF16 && ds.dtype != RLDA_BF16_KV8) || ds.d != D) return false;
   if (!(ds.scale > 0.f)) return false;                                  // the tile routine's softmax takes maxima before scaling
-  const int64_t B = (int64_t)ds.P * ds.G;
+  const int64_t B = n_sequences(ds), E = n_prefix_entries(ds);
   const int r = ds.Hq / ds.Hkv;
-  if (r > 16 || (int64_t)r * ds.G > MAX_GROUP_ROWS) return false;       // rows of one KV group: <= 4 parts of 64
-  if (ds.P + B + 1 > MAX_SCAN) return false;                            // the length scan lives in LDS
-  if ((int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK) > MAX_LINE ||
-      B * ds.Hkv * ceil_div(ds.Ls_cap, TK) > MAX_LINE) return false;       // 32-bit tile arithmetic
-  if ((int64_t)ds.Lp_cap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
+  if (r > 16 || (int64_t)r * max_group(ds) > MAX_GROUP_ROWS) return false;   // rows of one KV group: <= 4 parts of 64
+  if (E + B + 1 > MAX_SCAN) return false;                               // the length scan lives in LDS
+  int64_t ptiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK);
+  int64_t pcap = ds.Lp_cap;
+  if (ds.n_levels > 0) {
+    // the tree form: bf16 stores, contiguous suffix, one row part (the largest group has at most 64 query rows per KV head)
+    if (ds.dtype != RLDA_BF16 || ds.block_table || ds.seq_active || (int64_t)r * max_group(ds) > 64) return false;
+    ptiles = 0; pcap = 0;
+    for (int l = 0; l < ds.n_levels; ++l) {
+      ptiles += (int64_t)ds.levels[l].n_seg * ds.Hkv * ceil_div(ds.levels[l].cap, TK);
+      pcap = ds.levels[l].cap > pcap ? ds.levels[l].cap : pcap;
+    }
+  }
+  if (ptiles > MAX_LINE || B * ds.Hkv * ceil_div(ds.Ls_cap, TK) > MAX_LINE) return false;       // 32-bit tile arithmetic
+  if (pcap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
   return true;
 }
 
@@ -1350,9 +1413,21 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   P.cum = reinterpret_cast<int32_t*>(ws + L.cum);
   P.pl = reinterpret_cast<float*>(ws + L.pl); P.po = reinterpret_cast<_Float16*>(ws + L.po);
   P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<_Float16*>(ws + L.so);
-  P.P = ds.P; P.G = ds.G; P.B = ds.P * ds.G; P.Hq = ds.Hq; P.Hkv = ds.Hkv;
-  P.r = ds.Hq / ds.Hkv; P.R = P.r * ds.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
+  P.P = (int)n_prefix_entries(ds); P.G = max_group(ds); P.B = (int)n_sequences(ds); P.Hq = ds.Hq; P.Hkv = ds.Hkv;
+  P.r = ds.Hq / ds.Hkv; P.R = P.r * P.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
   P.c = ds.scale * 1.4426950408889634f;
+  const bool tree = ds.n_levels > 0;
+  P.n_lev = ds.n_levels;
+  for (int l = 0, first = 0; l < MAX_LEVELS; ++l) {
+    if (l < ds.n_levels) {
+      const Problem::Level& lv = ds.levels[l];
+      P.lev[l] = TreeLevel{static_cast<const char*>(lv.k), static_cast<const char*>(lv.v), lv.lens, first, lv.group,
+                           P.r * lv.group, lv.cap};
+      first += lv.n_seg;
+    } else {
+      P.lev[l] = TreeLevel{nullptr, nullptr, nullptr, 0x7fffffff, 1, 0, 0};
+    }
+  }
 
   // row halves of the KV group, and wavefronts per prefix tile (NRB 16-row blocks, a power of two)
   P.NH = row_parts(P.R);
@@ -1375,7 +1450,10 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
       partial_kernel<1, 1, true, true>,   partial_kernel<2, 1, true, true>,   partial_kernel<4, 1, true, true>,
       partial_kernel<4, 1, false, false, true>, partial_kernel<4, 1, true, false, true>,
       partial_kernel<4, 1, false, true, true>,  partial_kernel<4, 1, true, true, true>};
-  const kern_t kern = P.NH > 1 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
+  static const kern_t tree_kerns[3] = {partial_kernel<1, 1, false, false, false, true>, partial_kernel<2, 1, false, false, false, true>,
+                                       partial_kernel<4, 1, false, false, false, true>};
+  const kern_t kern = tree ? tree_kerns[nrb == 1 ? 0 : nrb == 2 ? 1 : 2]
+                    : P.NH > 1 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
                                : kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
   // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
   {
@@ -1386,8 +1464,8 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      for (int i = 0; i < 16; ++i) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kerns[i]),
+      for (int i = 0; i < 16 + 3; ++i) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(i < 16 ? kerns[i] : tree_kerns[i - 16]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }
@@ -1402,7 +1480,9 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
     if (e != hipSuccess) return e;
   }
   const int rows = P.B * P.Hq;
-  if ((int64_t)ds.P * P.HkvP >= COMBINE16_MIN_UNITS) {
+  if (tree) {
+    hipLaunchKernelGGL((combine_kernel<false, true>), dim3((rows + 7) / 8), dim3(256), 0, stream, P);
+  } else if ((int64_t)ds.P * P.HkvP >= COMBINE16_MIN_UNITS) {
     if (ext) hipLaunchKernelGGL(combine16_kernel<true>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
     else     hipLaunchKernelGGL(combine16_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
   } else {

@@ -150,6 +150,31 @@ def make_inputs(w: Workload, threads: int = 8) -> dict:
     }
 
 
+def make_tree_inputs(seed: int, B: int, Hq: int, Hkv: int, d: int, levels, Ls_cap: int, suffix: tuple,
+                     q_gain: float = 1.0, empty: float = 0.0, threads: int = 8) -> dict:
+    """One batch for the tree form: shared segments on several levels plus the own suffixes (bf16).
+
+    ``levels``: list of (group, cap, length kind as in Workload.prefix / suffix); level l has B // group
+    segments.  ``empty``: fraction of segments and suffixes whose length is forced to zero.  Returns
+    ``q``, ``k_suffix``, ``v_suffix``, ``suffix_lens`` and ``levels`` = [(k, v, lens, group)].
+    Stands in for a multi-turn rollout (Sec. 5.1, tasks (4)-(5)): the prompt shared by the whole group,
+    a first turn (tool call and observation) shared by a sub-group, then each trajectory's own tokens.
+    """
+    rng = np.random.default_rng(seed)
+    lens = []
+    for group, cap, kind in levels:
+        n = B // group
+        lens.append((_draw_lens(rng, kind, n, cap) * (rng.random(n) >= empty)).astype(np.int32))
+    suffix_lens = (_draw_lens(rng, suffix, B, Ls_cap) * (rng.random(B) >= empty)).astype(np.int32)
+    t = lambda i, shape, gain=1.0: _normal_tensor(seed, i, shape, "bf16", gain, threads)
+    out = {"q": t(0, (B, Hq, d), q_gain), "k_suffix": t(1, (B, Hkv, Ls_cap, d)), "v_suffix": t(2, (B, Hkv, Ls_cap, d)),
+           "suffix_lens": suffix_lens, "levels": []}
+    for i, ((group, cap, _), ln) in enumerate(zip(levels, lens)):
+        n = B // group
+        out["levels"].append((t(3 + 2 * i, (n, Hkv, cap, d)), t(4 + 2 * i, (n, Hkv, cap, d)), ln, group))
+    return out
+
+
 E4M3_MAX = 448.0          # largest finite e4m3 value
 
 

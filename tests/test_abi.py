@@ -321,3 +321,31 @@ def test_static_entry_point_validates_on_the_host_and_knows_its_limit():
     assert B.rl_decode_attn_static_raw(bad) == B.RLDA_ERR_STRUCT_SIZE
     assert B.rl_decode_attn_static_raw(good()) == B.RLDA_ERR_INVALID     # fits, but q / lengths / out are NULL
     assert B.rl_decode_attn_static_raw(good(P=0)) == B.RLDA_OK           # empty batch: nothing to do
+
+
+def test_tree_descriptor_layout_and_host_side_validation():
+    # 9 four-byte fields, padding to 8, four levels of 3 pointers + 2 ints, 6 pointers, pointer + size_t
+    assert ctypes.sizeof(B.rlda_tree_level) == 32
+    assert ctypes.sizeof(B.rlda_tree_desc) == 40 + 4 * 32 + 6 * 8 + 16
+    lv = lambda g, cap: (None, None, None, g, cap)
+    ok = B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(8, 300), lv(4, 100)])
+    assert B.rl_decode_attn_tree_workspace_bytes(ok) > 0
+    assert B.rl_decode_attn_tree_raw(ok) == B.RLDA_ERR_INVALID                  # supported, but every pointer is NULL
+    # a group that does not divide the batch, a negative capacity, too many levels
+    assert B.rl_decode_attn_tree_raw(B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(5, 300)])) == B.RLDA_ERR_INVALID
+    assert B.rl_decode_attn_tree_raw(B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(8, -1)])) == B.RLDA_ERR_INVALID
+    bad = B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(8, 300)])
+    bad.n_levels = 5
+    assert B.rl_decode_attn_tree_raw(bad) == B.RLDA_ERR_INVALID
+    bad = B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(8, 300)])
+    bad.struct_size = 16
+    assert B.rl_decode_attn_tree_raw(bad) == B.RLDA_ERR_STRUCT_SIZE
+    # outside what the tree form runs on: more than 64 query rows per segment and KV head, fp32, d = 64, scale <= 0, no level
+    for d_ in (B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [lv(16, 300)]),
+               B.make_tree_desc(B.RLDA_F32, 64, 28, 4, 128, 512, 0.088, [lv(8, 300)]),
+               B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 64, 512, 0.088, [lv(8, 300)]),
+               B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, -1.0, [lv(8, 300)]),
+               B.make_tree_desc(B.RLDA_BF16, 64, 28, 4, 128, 512, 0.088, [])):
+        assert B.rl_decode_attn_tree_raw(d_) == B.RLDA_ERR_UNSUPPORTED
+        assert B.rl_decode_attn_tree_workspace_bytes(d_) == 0
+    assert B.rl_decode_attn_tree_raw(B.make_tree_desc(B.RLDA_BF16, 0, 28, 4, 128, 512, 0.088, [lv(8, 300)])) == B.RLDA_OK
