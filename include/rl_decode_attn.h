@@ -337,6 +337,22 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
                                        int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
                                        int64_t* n_parts);
 
+/*
+ * The same for a device with `compute_units` compute units (rl_decode_attn_debug_partition is the case
+ * of 256, a whole MI355X).  The shared-prefix path asks the device for its compute-unit count at the
+ * first call and runs two workgroups on each of n pairs, n = rl_decode_attn_debug_pairs(compute_units):
+ * the largest power of two that is at most the count and at most 256 (128, 64 or 32 on the
+ * partitions of an MI355X), so the work is split for the device at hand; on other counts the split
+ * is still exact, only less even.  Workgroup numbers in `runs` / `parts` are then below 2 n, and the
+ * second workgroup of pair c is n + c.  Pure host functions.
+ */
+int32_t rl_decode_attn_debug_pairs(int32_t compute_units);   /* RLDA_ERR_INVALID below 1 */
+int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int32_t G, int32_t Hkv,
+                                          int32_t rows_per_kv_group, int32_t Lp_cap, int32_t Ls_cap,
+                                          const int32_t* prefix_lens, const int32_t* suffix_lens,
+                                          int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
+                                          int64_t* n_parts);
+
 #ifdef __cplusplus
 }
 #endif

@@ -284,13 +284,26 @@ int rl_lse_combine(const float* o_parts, const float* lse_parts, int32_t n_parts
   return e == hipSuccess ? RLDA_OK : RLDA_ERR_LAUNCH;
 }
 
+int32_t rl_decode_attn_debug_pairs(int32_t compute_units) {
+  return compute_units < 1 ? RLDA_ERR_INVALID : rlda::pairs_for(compute_units);
+}
+
 int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_t rows_per_kv_group,
                                        int32_t Lp_cap, int32_t Ls_cap, const int32_t* prefix_lens, const int32_t* suffix_lens,
                                        int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
                                        int64_t* n_parts) {
+  return rl_decode_attn_debug_partition_on(256, P, G, Hkv, rows_per_kv_group, Lp_cap, Ls_cap, prefix_lens, suffix_lens,
+                                           runs, runs_cap, parts, parts_cap, n_parts);
+}
+
+int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int32_t G, int32_t Hkv, int32_t rows_per_kv_group,
+                                          int32_t Lp_cap, int32_t Ls_cap, const int32_t* prefix_lens, const int32_t* suffix_lens,
+                                          int32_t* runs, int64_t runs_cap, int32_t* parts, int64_t parts_cap,
+                                          int64_t* n_parts) {
   using namespace rlda;
-  if (P < 0 || G < 0 || Hkv <= 0 || rows_per_kv_group <= 0 || !prefix_lens || !suffix_lens || !n_parts)
+  if (P < 0 || G < 0 || Hkv <= 0 || rows_per_kv_group <= 0 || !prefix_lens || !suffix_lens || !n_parts || compute_units < 1)
     return RLDA_ERR_INVALID;
+  const int n_cu = pairs_for(compute_units);
   const int B = P * G;
   if (rows_per_kv_group > MAX_GROUP_ROWS) return RLDA_ERR_INVALID;
   const int HkvP = Hkv * row_parts(rows_per_kv_group);                  // prefix units per prompt: (KV head, row part)
@@ -300,7 +313,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
   for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
   for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
   const int cumP = X[P];
-  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, n_cu);
   int64_t nr = 0, np = 0;
   auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
     if (runs && nr < runs_cap) {
@@ -309,7 +322,7 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
     }
     ++nr;
   };
-  for (int w = 0; w < N_WG; ++w) {               // the partial kernel's walk
+  for (int w = 0; w < 2 * n_cu; ++w) {           // the partial kernel's walk
     int ilo, ihi, klo, khi;
     wg_prefix_range(sc, w, ilo, ihi);
     wg_suffix_range(sc, w, klo, khi);
@@ -340,12 +353,12 @@ int64_t rl_decode_attn_debug_partition(int32_t P, int32_t G, int32_t Hkv, int32_
   for (int p = 0; p < P; ++p)                    // the combine kernel's enumeration
     for (int j = 0; j < HkvP; ++j)
       for_each_prefix_part(sc, X.data(), HkvP, p, j, [&](int rank) {
-        put_part(0, p, j, rank % 2 ? N_CU + rank / 2 : rank / 2, -1, p * HkvP + j + rank);
+        put_part(0, p, j, rank % 2 ? n_cu + rank / 2 : rank / 2, -1, p * HkvP + j + rank);
       });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)
       for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j, [&](int rank, int v) {
-        put_part(1, b, j, rank % 2 ? N_CU + rank / 2 : rank / 2, v, b * Hkv + j + WG_WAVES * rank + v);
+        put_part(1, b, j, rank % 2 ? n_cu + rank / 2 : rank / 2, v, b * Hkv + j + WG_WAVES * rank + v);
       });
   *n_parts = np;
   return nr;

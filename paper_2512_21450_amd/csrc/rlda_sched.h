@@ -6,9 +6,12 @@
 // and owns ceil(Ls/TK) tiles.  Prefix tiles form one line (prompt-major, then KV
 // head, then tile), suffix tiles another (sequence-major, then KV head, then tile).
 //
-// The partial kernel runs 2 * N_CU workgroups, two per compute unit: workgroup
-// c ("A") and workgroup N_CU + c ("B") form pair c.  Every pair gets the same
-// share of each line (position N*c/N_CU .. N*(c+1)/N_CU), so that every compute
+// The partial kernel runs 2 * n_cu workgroups, two per compute unit: workgroup
+// c ("A") and workgroup n_cu + c ("B") form pair c.  n_cu is the largest power of
+// two that is at most the device's compute-unit count and at most N_CU (256 on a
+// whole MI355X; 128, 64 or 32 when the device is one partition of it), so that
+// the share arithmetic is shifts.  Every pair gets the same
+// share of each line (position N*c/n_cu .. N*(c+1)/n_cu), so that every compute
 // unit carries the same mix of work and all finish together.  Inside a pair the
 // two workgroups are evened out by tile weight (a prefix tile costs wP, a suffix
 // tile wS): in a batch whose suffix tiles outweigh its prefix tiles, A takes all
@@ -33,8 +36,16 @@ namespace rlda {
 
 constexpr int TK = 32;            // keys per tile
 constexpr int WG_WAVES = 4;       // wavefronts per workgroup
-constexpr int N_CU = 256;         // workgroup pairs: one per compute unit
-constexpr int N_WG = 2 * N_CU;    // workgroups of the partial kernel
+constexpr int N_CU = 256;         // most workgroup pairs: one per compute unit of a whole MI355X
+constexpr int N_WG = 2 * N_CU;    // most workgroups of the partial kernel (workspaces are sized for it)
+constexpr int CU_PER_DIE = 32;    // compute units per die: workgroup i is dispatched to die i % (n_cu / 32)
+
+// workgroup pairs the kernels use on a device with `compute_units` compute units (>= 1)
+__host__ __device__ inline int pairs_for(int compute_units) {
+  int n = 1;
+  while (2 * n <= compute_units && 2 * n <= N_CU) n *= 2;
+  return n;
+}
 constexpr int PREFIX_WEIGHT = 6;  // cost of a prefix tile ...
 constexpr int SUFFIX_WEIGHT = 4;  // ... relative to a suffix tile, when the batch saturates the memory system
 // A batch of fewer tiles than this (256 MB of K/V) does not: its suffix tiles then come back in half the
@@ -47,7 +58,8 @@ struct Sched {
   int NPT;      // prefix tiles in total (all units)
   int NST;      // suffix tiles in total
   int wP, wS;   // tile weights
-  int n_cu;     // workgroup pairs
+  int n_cu;     // workgroup pairs, a power of two
+  int cu_sh;    // its logarithm
   bool heavy;   // the prefix tiles outweigh the suffix tiles: B workgroups share them, A takes no suffix
 };
 
@@ -63,6 +75,8 @@ __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? l
 __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {
   Sched s;
   s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_cu = n_cu;
+  s.cu_sh = 0;
+  while ((1 << s.cu_sh) < n_cu) ++s.cu_sh;
   s.heavy = wP * NPT > wS * NST;               // lines are at most MAX_LINE tiles: no overflow
   s.wP = !s.heavy && NPT + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : wP;
   return s;
@@ -72,48 +86,48 @@ __host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, in
 // division is slow on the GPU and the combine kernel does several per row).
 constexpr int MAX_LINE = (1 << 30) / N_CU;
 
-// pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles
-__host__ __device__ inline int share(int N, int c, int n_cu) { return (int)(((unsigned)N * (unsigned)c) / (unsigned)n_cu); }
+// pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles (cu_sh = log2 of the pair count)
+__host__ __device__ inline int share(int N, int c, int cu_sh) { return (int)(((unsigned)N * (unsigned)c) >> cu_sh); }
 // the pair that owns position i: the largest c with share(N, c) <= i
-__host__ __device__ inline int share_owner(int N, int i, int n_cu) {
-  return (int)((((unsigned)(i + 1) * (unsigned)n_cu) + (unsigned)N - 1u) / (unsigned)N) - 1;
+__host__ __device__ inline int share_owner(int N, int i, int cu_sh) {
+  return (int)(((((unsigned)(i + 1)) << cu_sh) + (unsigned)N - 1u) / (unsigned)N) - 1;
 }
 
 // prefix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  B gets some only
 // in a prefix-heavy batch, and then as many as even out the pair.
 __host__ __device__ inline void pair_prefix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
-  lo = share(s.NPT, c, s.n_cu);
-  hi = share(s.NPT, c + 1, s.n_cu);
+  lo = share(s.NPT, c, s.cu_sh);
+  hi = share(s.NPT, c + 1, s.cu_sh);
   mid = hi;
   if (s.heavy) {
-    const int ns = share(s.NST, c + 1, s.n_cu) - share(s.NST, c, s.n_cu);
+    const int ns = share(s.NST, c + 1, s.cu_sh) - share(s.NST, c, s.cu_sh);
     mid = hi - clampi((s.wP * (hi - lo) - s.wS * ns) / (2 * s.wP), 0, hi - lo);
   }
 }
 __host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
   int a, m, b;
-  pair_prefix_range(s, w % s.n_cu, a, m, b);
+  pair_prefix_range(s, w & (s.n_cu - 1), a, m, b);
   if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
 }
-__host__ __device__ inline int prefix_tile_pair(const Sched& s, int i) { return share_owner(s.NPT, i, s.n_cu); }
+__host__ __device__ inline int prefix_tile_pair(const Sched& s, int i) { return share_owner(s.NPT, i, s.cu_sh); }
 
 // suffix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  A gets some only
 // in a suffix-heavy batch, and then as many as even out the pair.
 __host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
-  lo = share(s.NST, c, s.n_cu);
-  hi = share(s.NST, c + 1, s.n_cu);
+  lo = share(s.NST, c, s.cu_sh);
+  hi = share(s.NST, c + 1, s.cu_sh);
   mid = lo;
   if (!s.heavy) {
-    const int np = share(s.NPT, c + 1, s.n_cu) - share(s.NPT, c, s.n_cu);
+    const int np = share(s.NPT, c + 1, s.cu_sh) - share(s.NPT, c, s.cu_sh);
     mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
   }
 }
 __host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
   int a, m, b;
-  pair_suffix_range(s, w % s.n_cu, a, m, b);
+  pair_suffix_range(s, w & (s.n_cu - 1), a, m, b);
   if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
 }
-__host__ __device__ inline int suffix_tile_pair(const Sched& s, int k) { return share_owner(s.NST, k, s.n_cu); }
+__host__ __device__ inline int suffix_tile_pair(const Sched& s, int k) { return share_owner(s.NST, k, s.cu_sh); }
 
 // run of wavefront v inside the workgroup's suffix range
 __host__ __device__ inline void wave_suffix_range(int lo, int hi, int v, int& a, int& b) {

@@ -43,7 +43,6 @@ constexpr int STAGE_B = 2 * TILE_B;               // K tile + V tile
 constexpr int NTHREADS = 64 * WG_WAVES;
 constexpr int LDS_BYTES = WG_WAVES * STAGE_B;     // 64 KB: one stage per wavefront, two workgroups per CU
 constexpr int MAX_SCAN = LDS_BYTES / 4;           // ints of LDS available to the length scan
-constexpr int N_XCD = 8;                          // compute dies; workgroup i is dispatched to die i % N_XCD
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -85,6 +84,7 @@ struct SharedParams {
   // level after level, P is their total number, G and R are the largest group's, kp / vp / plens are unused
   TreeLevel lev[MAX_LEVELS];
   int n_lev;
+  int n_cu;               // workgroup pairs (pairs_for the device's compute units); the grid is 2 * n_cu workgroups
 };
 
 // the level that entry `e` of the prefix line belongs to (e is wavefront-uniform: scalar selects)
@@ -782,7 +782,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -808,12 +808,12 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
     cur_load(c, [&](int b) { return slen_of<EXT>(P, b); });
-    // Workgroup i runs on die i % N_XCD.  The first wavefront of the first workgroup on each die writes that
+    // Workgroup i runs on die i % (n_cu / CU_PER_DIE).  The first wavefront of the first workgroup on each die writes that
     // die's L2 back when its first suffix tile has landed: the workgroups of the die have stored their prefix
     // partials by then (all carry the same number of prefix tiles).  A wrong guess about which die a workgroup
     // is on only makes the write-back less useful.
     suffix_stream<EXT, F8>(P, lds + wv * STAGE_B, c, kb - ka, WG_WAVES * wg_rank(sc, w) + wv, lane,
-                           ilo < ihi && w < N_XCD && wv == 0);
+                           ilo < ihi && w * CU_PER_DIE < P.n_cu && wv == 0);
   }
 }
 
@@ -835,7 +835,7 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
   const int half = P.NH > 1 ? grow >> 6 : 0;
   const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
@@ -948,7 +948,7 @@ __global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P)
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, N_CU);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
   const int half = P.NH > 1 ? grow >> 6 : 0;
   const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
@@ -1043,7 +1043,7 @@ template <int NTP>                                          // 16-row blocks per
 __global__ void __launch_bounds__(NTHREADS, 2) prefill_kernel(const PrefillParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  constexpr int WROWS = 16 * NTP;                           // rows per wavefront
+  constexpr int N_XCD = 8, WROWS = 16 * NTP;                // rows per wavefront
   const int units = P.P * P.Hkv;
   const int xcd = blockIdx.x % N_XCD, seq = blockIdx.x / N_XCD;
   const int pj = (seq / P.nqb) * N_XCD + xcd, qb = P.nqb - 1 - seq % P.nqb;
@@ -1232,7 +1232,7 @@ template <int NTP>
 __global__ void __launch_bounds__(NTHREADS, 2) prefill2_kernel(const PrefillParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  constexpr int WROWS = 16 * NTP;
+  constexpr int N_XCD = 8, WROWS = 16 * NTP;
   const int units = P.P * P.Hkv;
   const int xcd = blockIdx.x % N_XCD, seq = blockIdx.x / N_XCD;
   const int pj = (seq / P.nqb) * N_XCD + xcd, qb = P.nqb - 1 - seq % P.nqb;
@@ -1382,7 +1382,9 @@ bool shared_supported(const Problem& ds) {
   const int64_t B = n_sequences(ds), E = n_prefix_entries(ds);
   const int r = ds.Hq / ds.Hkv;
   if (r > 16 || (int64_t)r * max_group(ds) > MAX_GROUP_ROWS) return false;   // rows of one KV group: <= 4 parts of 64
-  if (E + B + 1 > MAX_SCAN) return false;                               // the length scan lives in LDS
+  // The scan of tile counts lives in LDS.  A batch with more prompts and sequences than it holds is run as
+  // several launches over whole prompts (max_prompts_per_launch); the tree form has to fit as it is.
+  if (ds.n_levels > 0 ? E + B + 1 > MAX_SCAN : ds.G + 2 > MAX_SCAN) return false;
   int64_t ptiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK);
   int64_t pcap = ds.Lp_cap;
   if (ds.n_levels > 0) {
@@ -1399,9 +1401,55 @@ bool shared_supported(const Problem& ds) {
   return true;
 }
 
-size_t shared_workspace_bytes(const Problem& ds) { return layout(ds).total; }
+// prompts one launch can take: their count, their sequences and one more entry fit the LDS scan
+int max_prompts_per_launch(const Problem& ds) {
+  if (ds.n_levels > 0) return ds.P;
+  const int64_t fit = (MAX_SCAN - 1) / ((int64_t)ds.G + 1);
+  return (int)(fit < ds.P ? fit : ds.P);
+}
 
-hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) {
+// prompts [p0, p0 + np) of a batch as a batch of its own
+Problem prompt_range(const Problem& ds, int p0, int np) {
+  Problem s = ds;
+  const size_t kvb = kv_elem_bytes(ds.dtype), qb = ds.dtype == RLDA_F32 ? 4 : 2;
+  const size_t b0 = (size_t)p0 * ds.G;
+  auto adv = [](const void* p, size_t bytes) { return p ? static_cast<const void*>(static_cast<const char*>(p) + bytes) : p; };
+  s.P = np;
+  s.q = adv(ds.q, b0 * ds.Hq * ds.d * qb);
+  s.k_prefix = adv(ds.k_prefix, (size_t)p0 * ds.Hkv * ds.Lp_cap * ds.d * kvb);
+  s.v_prefix = adv(ds.v_prefix, (size_t)p0 * ds.Hkv * ds.Lp_cap * ds.d * kvb);
+  s.prefix_lens = ds.prefix_lens + p0;
+  if (ds.block_table) {                                     // the page pools are shared; the table rows move
+    s.block_table = ds.block_table + b0 * ds.max_pages;
+  } else {
+    s.k_suffix = adv(ds.k_suffix, b0 * ds.Hkv * ds.Ls_cap * ds.d * kvb);
+    s.v_suffix = adv(ds.v_suffix, b0 * ds.Hkv * ds.Ls_cap * ds.d * kvb);
+  }
+  s.suffix_lens = ds.suffix_lens + b0;
+  if (ds.seq_active) s.seq_active = ds.seq_active + b0;
+  s.out = ds.out + b0 * ds.Hq * ds.d;
+  if (ds.lse) s.lse = ds.lse + b0 * ds.Hq;
+  return s;
+}
+
+size_t shared_workspace_bytes(const Problem& ds) {
+  const int np = max_prompts_per_launch(ds);
+  return layout(np < ds.P ? prompt_range(ds, 0, np) : ds).total;
+}
+
+hipError_t launch_shared(const Problem& whole, hipStream_t stream, hipEvent_t mid) {
+  // more prompts and sequences than one launch takes: whole prompts at a time, one after the other on the stream
+  // (they share the workspace)
+  const int np_max = max_prompts_per_launch(whole);
+  if (np_max < whole.P) {
+    for (int p0 = 0; p0 < whole.P; p0 += np_max) {
+      const int np = whole.P - p0 < np_max ? whole.P - p0 : np_max;
+      const hipError_t e = launch_shared(prompt_range(whole, p0, np), stream, p0 + np == whole.P ? mid : nullptr);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  const Problem& ds = whole;
   const Layout L = layout(ds);
   char* ws = static_cast<char*>(ds.workspace);
   SharedParams P;
@@ -1455,24 +1503,34 @@ hipError_t launch_shared(const Problem& ds, hipStream_t stream, hipEvent_t mid) 
   const kern_t kern = tree ? tree_kerns[nrb == 1 ? 0 : nrb == 2 ? 1 : 2]
                     : P.NH > 1 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
                                : kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
-  // a kernel that uses more than 64 KB of LDS in total needs an opt-in, once per device
+  // once per device: the compute-unit count decides the workgroup pairs; a kernel that uses more than 64 KB of
+  // LDS in total needs an opt-in
   {
     static std::mutex mu;
     static bool done[64] = {};
+    static int pairs[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
+      int cus = 0;
+      e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e != hipSuccess) return e;
+      if (cus < 1) return hipErrorInvalidDevice;
+      if (dev >= 0 && dev < 64) pairs[dev] = pairs_for(cus);
+      P.n_cu = pairs_for(cus);
       for (int i = 0; i < 16 + 3; ++i) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(i < 16 ? kerns[i] : tree_kerns[i - 16]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }
       if (dev >= 0 && dev < 64) done[dev] = true;
+    } else {
+      P.n_cu = pairs[dev];
     }
   }
-  hipLaunchKernelGGL(kern, dim3(N_WG), dim3(NTHREADS), LDS_BYTES, stream, P);
+  hipLaunchKernelGGL(kern, dim3(2 * P.n_cu), dim3(NTHREADS), LDS_BYTES, stream, P);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (mid) {

@@ -349,3 +349,58 @@ def test_tree_descriptor_layout_and_host_side_validation():
         assert B.rl_decode_attn_tree_raw(d_) == B.RLDA_ERR_UNSUPPORTED
         assert B.rl_decode_attn_tree_workspace_bytes(d_) == 0
     assert B.rl_decode_attn_tree_raw(B.make_tree_desc(B.RLDA_BF16, 0, 28, 4, 128, 512, 0.088, [lv(8, 300)])) == B.RLDA_OK
+
+
+def _cpu_case(**over):
+    import torch
+    P, G, Hq, Hkv, d, Lp, Ls = 2, 3, 4, 2, 128, 40, 24
+    t = dict(q=torch.zeros(P * G, Hq, d, dtype=torch.bfloat16),
+             k_prefix=torch.zeros(P, Hkv, Lp, d, dtype=torch.bfloat16), v_prefix=torch.zeros(P, Hkv, Lp, d, dtype=torch.bfloat16),
+             prefix_lens=torch.zeros(P, dtype=torch.int32),
+             k_suffix=torch.zeros(P * G, Hkv, Ls, d, dtype=torch.bfloat16), v_suffix=torch.zeros(P * G, Hkv, Ls, d, dtype=torch.bfloat16),
+             suffix_lens=torch.zeros(P * G, dtype=torch.int32),
+             out=torch.zeros(P * G, Hq, d), lse=torch.zeros(P * G, Hq))
+    t.update(over)
+    return t, G
+
+
+def _desc(t, G):
+    return B.desc_from_tensors(t["q"], t["k_prefix"], t["v_prefix"], t["prefix_lens"], t["k_suffix"], t["v_suffix"],
+                               t["suffix_lens"], 0.1, G, t["out"], t["lse"])
+
+
+def test_descriptor_helper_rejects_what_the_kernels_would_misread():
+    import torch
+    t, G = _cpu_case()
+    assert _desc(t, G).P == 2                                   # the well-formed case goes through
+    for over, exc in [
+        (dict(suffix_lens=torch.zeros(6, dtype=torch.int64)), TypeError),      # torch's default integer: read as pairs of int32
+        (dict(prefix_lens=torch.zeros(2, dtype=torch.int64)), TypeError),
+        (dict(suffix_lens=torch.zeros(5, dtype=torch.int32)), ValueError),     # one length per sequence
+        (dict(prefix_lens=torch.zeros(3, dtype=torch.int32)), ValueError),
+        (dict(out=torch.zeros(6, 4, 128, dtype=torch.bfloat16)), TypeError),   # out is written as fp32
+        (dict(out=torch.zeros(6, 4, 64)), ValueError),                         # too small: would be overrun
+        (dict(lse=torch.zeros(6, 4, dtype=torch.float64)), TypeError),
+        (dict(lse=torch.zeros(6, 3)), ValueError),
+        (dict(v_prefix=torch.zeros(2, 2, 39, 128, dtype=torch.bfloat16)), ValueError),
+        (dict(v_suffix=torch.zeros(6, 2, 25, 128, dtype=torch.bfloat16)), ValueError),
+        (dict(out=torch.zeros(6, 4, 256)[:, :, ::2]), ValueError),             # not contiguous
+    ]:
+        t, G = _cpu_case(**over)
+        with pytest.raises(exc):
+            _desc(t, G)
+
+
+def test_tree_descriptor_helper_rejects_misshaped_levels():
+    import torch
+    t, G = _cpu_case()
+    lv = lambda n, g, dt=torch.int32: (torch.zeros(n, 2, 16, 128, dtype=torch.bfloat16), torch.zeros(n, 2, 16, 128, dtype=torch.bfloat16),
+                                       torch.zeros(n, dtype=dt), g)
+    mk = lambda levels: B.tree_desc_from_tensors(t["q"], levels, t["k_suffix"], t["v_suffix"], t["suffix_lens"], 0.1, t["out"], t["lse"])
+    assert mk([lv(2, 3), lv(3, 2)]).n_levels == 2
+    with pytest.raises(ValueError):
+        mk([lv(2, 2)])                                          # 2 segments x 2 sequences do not cover 6
+    with pytest.raises(TypeError):
+        mk([lv(2, 3, torch.int64)])
+    with pytest.raises(ValueError):
+        mk([lv(6, 1)] * 5)                                      # more levels than the descriptor holds

@@ -344,10 +344,11 @@ def test_two_level_shared_prefix_by_composition(B):
     util.compare(out.reshape(P * G, Hq, d), lse.reshape(P * G, Hq), ro, rl, "bf16", "two-level prefix")
 
 
-@pytest.mark.parametrize("P,plan", [(3000, "shared"), (3300, "simple")])
+@pytest.mark.parametrize("P,plan", [(3000, "shared"), (3300, "shared"), (7001, "shared")])
 def test_many_short_sequences_fill_the_length_scan(B, P, plan):
-    """Thousands of prompts and sequences: the in-kernel length scan and the owner search run at (and,
-    for the second case, beyond) their capacity, where the call falls back to the simple kernel."""
+    """Thousands of prompts and sequences: the in-kernel length scan and the owner search run at their
+    capacity (16 384 entries: 3000 prompts of 4 sequences fit, 3300 do not); beyond it the call stays on
+    the shared-prefix kernels and runs whole prompts in two or three launches."""
     import torch
     G, Hq, Hkv, d = 4, 4, 2, 128
     x = util.random_case(70 + P, P, G, Hq, Hkv, d, 40, 40, "bf16")

@@ -16,22 +16,37 @@ _f.argtypes = [ctypes.c_int32] * 6 + [ctypes.c_void_p] * 2 + [ctypes.c_void_p, c
                                                                ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
 
 
-def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
+_g = B._lib.rl_decode_attn_debug_partition_on
+_g.restype = ctypes.c_int64
+_g.argtypes = [ctypes.c_int32] * 7 + [ctypes.c_void_p] * 2 + [ctypes.c_void_p, ctypes.c_int64,
+                                                               ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+_pairs = B._lib.rl_decode_attn_debug_pairs
+_pairs.restype = ctypes.c_int32
+_pairs.argtypes = [ctypes.c_int32]
+
+
+def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8, cus=256):
     plens = np.ascontiguousarray(plens, np.int32)
     slens = np.ascontiguousarray(slens, np.int32)
     cap = 4 * (P * (G + 2) * Hkv + 8 * 512) + 16
     runs = np.zeros((cap, 8), np.int32)
     parts = np.zeros((cap, 6), np.int32)
     npart = ctypes.c_int64(0)
-    nr = _f(P, G, Hkv, R, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
-            parts.ctypes.data, cap, ctypes.byref(npart))
+    if cus == 256:
+        nr = _f(P, G, Hkv, R, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
+                parts.ctypes.data, cap, ctypes.byref(npart))
+    else:
+        nr = _g(cus, P, G, Hkv, R, Lp_cap, Ls_cap, plens.ctypes.data, slens.ctypes.data, runs.ctypes.data, cap,
+                parts.ctypes.data, cap, ctypes.byref(npart))
     assert 0 <= nr <= cap and npart.value <= cap
     return runs[:nr], parts[:npart.value]
 
 
-def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
-    """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half)."""
-    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R)
+def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8, cus=256):
+    """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half).
+    cus: compute units of the device the partition is made for."""
+    runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R, cus)
+    NC = _pairs(cus)                              # workgroup pairs
     HkvP = Hkv * (4 if R > 128 else 2 if R > 64 else 1)
     tp = -(-np.clip(plens, 0, Lp_cap) // TK)
     ts = -(-np.clip(slens, 0, Ls_cap) // TK)
@@ -56,6 +71,7 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
         sl = runs[runs[:, 0] == kind][:, 7]
         assert len(set(sl.tolist())) == len(sl)
         assert sl.size == 0 or (sl.min() >= 0 and sl.max() < nslots)
+    assert runs.shape[0] == 0 or (runs[:, 5].min() >= 0 and runs[:, 5].max() < 2 * NC)
     # the combine enumeration == the set of runs, and per unit in increasing line order
     key_r = sorted((int(k), int(m), int(j), int(w), int(v), int(s)) for k, m, j, _, _, w, v, s in runs)
     key_p = sorted(tuple(int(x) for x in row) for row in parts)
@@ -64,24 +80,24 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8):
     # an equal share of the prefix tiles and of the suffix tiles, up to rounding
     npt, nst = int(tp.sum()) * HkvP, int(ts.sum()) * Hkv
     for kind, total in ((0, npt), (1, nst)):
-        load = np.zeros(256, np.int64)
+        load = np.zeros(NC, np.int64)
         rk = runs[runs[:, 0] == kind]
-        np.add.at(load, rk[:, 5] % 256, rk[:, 4])
+        np.add.at(load, rk[:, 5] % NC, rk[:, 4])
         assert load.sum() == total
-        assert load.max() <= -(-total // 256) and load.min() >= total // 256
+        assert load.max() <= -(-total // NC) and load.min() >= total // NC
     # inside a pair the heavier line is shared: the second workgroup has prefix tiles only if the first
     # has no suffix tiles, and the two then differ by less than two tiles' weight
     WP, WS = (14 if npt + nst < 16384 and 6 * npt <= 4 * nst else 6), 4   # small suffix-heavy batches weigh prefix tiles more
-    wa, wb = np.zeros(256, np.int64), np.zeros(256, np.int64)
-    a_suffix, b_prefix = np.zeros(256, np.int64), np.zeros(256, np.int64)
+    wa, wb = np.zeros(NC, np.int64), np.zeros(NC, np.int64)
+    a_suffix, b_prefix = np.zeros(NC, np.int64), np.zeros(NC, np.int64)
     for kind, _, _, _, n, w, _, _ in runs:
         wt = n * (WP if kind == 0 else WS)
-        if w < 256:
+        if w < NC:
             wa[w] += wt
             a_suffix[w] += n if kind == 1 else 0
         else:
-            wb[w - 256] += wt
-            b_prefix[w - 256] += n if kind == 0 else 0
+            wb[w - NC] += wt
+            b_prefix[w - NC] += n if kind == 0 else 0
     assert not ((a_suffix > 0) & (b_prefix > 0)).any()
     shared = (a_suffix > 0) | (b_prefix > 0)
     assert (np.abs(wa - wb)[shared] <= 2 * max(WP, WS)).all()
@@ -136,3 +152,29 @@ def test_partition_edge_cases():
         pl = rng.integers(0, Lp_cap + 1, P) * (rng.random(P) < 0.8)
         sl = rng.integers(0, Ls_cap + 1, P * G) * (rng.random(P * G) < 0.7)
         check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128, 129, 256])))
+
+
+def test_pairs_follow_the_compute_unit_count():
+    # the largest power of two that is at most the device's compute units and at most 256
+    assert [_pairs(c) for c in (256, 304, 255, 128, 100, 64, 33, 32, 2, 1)] == [256, 256, 128, 128, 64, 64, 32, 32, 2, 1]
+    assert _pairs(0) < 0 and _pairs(-3) < 0
+
+
+@pytest.mark.parametrize("cus", [128, 64, 32, 100, 1])
+def test_partition_for_other_compute_unit_counts(cus):
+    """A partition of the chip (128, 64 or 32 compute units) or any other count: every tile once, slots
+    unique and inside the workspace, the combine reads what the walk writes, pairs evenly loaded."""
+    w = wl.WORKLOADS["vlm7b"]
+    rng = np.random.default_rng(w.seed)
+    pl = wl._draw_lens(rng, w.prefix, w.P, w.Lp_cap)
+    sl = wl._draw_lens(rng, w.suffix, w.B, w.Ls_cap)
+    check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, pl, sl, R=w.G * w.Hq // w.Hkv, cus=cus)
+    check(w.P, w.G, w.Hkv, w.Lp_cap, w.Ls_cap, [w.Lp_cap] * w.P, [5] * w.B, cus=cus)
+    check(3, 2, 4, 100, 100, [100, 0, 31], [0, 100, 1, 32, 33, 0], cus=cus)
+    rng = np.random.default_rng(cus)
+    for _ in range(6):
+        P, G, Hkv = int(rng.integers(1, 40)), int(rng.integers(1, 9)), int(rng.integers(1, 5))
+        Lp_cap, Ls_cap = int(rng.integers(0, 3000)), int(rng.integers(0, 5000))
+        pl = rng.integers(0, Lp_cap + 1, P) * (rng.random(P) < 0.8)
+        sl = rng.integers(0, Ls_cap + 1, P * G) * (rng.random(P * G) < 0.7)
+        check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128, 129, 256])), cus=cus)
