@@ -24,7 +24,9 @@ With z = logits / T and w = ref_logits / T (both widened to fp64):
   kl       = sum_i p_i (ln p_i - ln r_i)    with r_i = exp(w_i - lse_w)
 A logit of -inf (a masked token) has p_i = 0 and contributes nothing to the
 entropy and KL sums (the limit p ln p -> 0); a row must keep at least one
-finite logit.  Everything is written out as these definitions, in numpy fp64,
+finite logit.  A NaN logit is read as a masked token as well (a reading: the
+paper says nothing about invalid logits; a mask is the one meaning under which
+the other tokens of the row still have a distribution).  Everything is written out as these definitions, in numpy fp64,
 one row at a time; nothing is fused or reordered.
 """
 from __future__ import annotations
@@ -50,6 +52,7 @@ def token_stats_ref(logits, token_ids, inv_temperature=1.0, ref_logits=None):
         out["kl"] = np.zeros(n)
     for b in range(n):
         z = _widen(logits[b]) * float(inv_temperature)
+        z = np.where(np.isnan(z), -np.inf, z)       # NaN: a masked token
         m = z.max()
         lse = m + np.log(np.exp(z - m).sum())
         logp = z - lse                              # ln p_i
@@ -64,6 +67,7 @@ def token_stats_ref(logits, token_ids, inv_temperature=1.0, ref_logits=None):
             out["logprob"][b] = logp[y]
         if ref_logits is not None:
             w = _widen(ref_logits[b]) * float(inv_temperature)
+            w = np.where(np.isnan(w), -np.inf, w)
             mw = w.max()
             logr = w - (mw + np.log(np.exp(w - mw).sum()))
             out["kl"][b] = (p[live] * (logp[live] - logr[live])).sum()

@@ -165,3 +165,23 @@ def test_masked_logits_are_the_distribution_over_the_rest():
     c = token_stats_ref(m, ids_full, ref_logits=mr)
     assert np.allclose(c["kl"], b["kl"], atol=1e-13) and np.allclose(c["ref_logprob"], b["ref_logprob"], atol=1e-13)
     assert np.isneginf(token_stats_ref(m, [3, 3])["logprob"]).all()
+
+
+def test_nan_logits_are_read_as_masked_tokens():
+    # the reading the header states: a NaN logit is a masked token; the rest of the row keeps its distribution
+    rng = np.random.default_rng(13)
+    lg = rng.standard_normal((3, 30)).astype(np.float32)
+    rf = rng.standard_normal((3, 30)).astype(np.float32)
+    bad, ref_bad = lg.copy(), rf.copy()
+    bad[:, [2, 11, 29]] = np.nan
+    ref_bad[:, [2, 11, 29]] = np.nan
+    inf, ref_inf = lg.copy(), rf.copy()
+    inf[:, [2, 11, 29]] = -np.inf
+    ref_inf[:, [2, 11, 29]] = -np.inf
+    ids = np.array([0, 11, 12])
+    a = token_stats_ref(bad, ids, 0.7, ref_logits=ref_bad)
+    b = token_stats_ref(inf, ids, 0.7, ref_logits=ref_inf)
+    for k in a:
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
+    assert np.isfinite(a["lse"]).all() and np.isfinite(a["entropy"]).all() and np.isfinite(a["kl"]).all()
+    assert np.isneginf(a["logprob"][1]) and np.isfinite(a["logprob"][[0, 2]]).all()   # the sampled token itself masked
