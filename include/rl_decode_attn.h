@@ -30,9 +30,14 @@
  * How it is computed: the prefix K/V of a prompt is read from HBM once and
  * reused by all G samples and all Hq/Hkv query heads of a KV group; each
  * sequence's suffix is streamed once; partial (o, lse) results of key ranges
- * are merged by a log-sum-exp combine.  The result is exact up to fp32
- * rounding order (bf16 inputs: softmax weights are rounded to bf16 before the
- * value contraction, accumulation is fp32).
+ * are merged by a log-sum-exp combine.  The method is exact; what the result
+ * carries is rounding.  fp32 inputs: fp32 rounding order only.  bf16 inputs:
+ * scores and sums accumulate in fp32, the softmax weights are rounded to bf16
+ * before the value contraction, and a partial result passes between the two
+ * kernels as fp16 after a per-row power-of-two scaling that puts its largest
+ * magnitude into [0.5, 1) (an error of at most 2^-12 of that magnitude per
+ * element).  Observed against the fp64 definition on the benchmark shapes:
+ * 1e-3 on out, 1e-6 on lse.
  */
 #ifndef RL_DECODE_ATTN_H
 #define RL_DECODE_ATTN_H
@@ -65,7 +70,13 @@ typedef enum { RLDA_F32 = 0, RLDA_BF16 = 1, RLDA_BF16_KV8 = 2 } rlda_dtype;
 
 /* Kernel selection. */
 typedef enum {
-  RLDA_ALGO_AUTO = 0,      /* shared-prefix MFMA path when the shape allows it (and scale > 0), else SIMPLE */
+  RLDA_ALGO_AUTO = 0,      /* shared-prefix MFMA path when the shape allows it, else SIMPLE.  The fast path
+                              takes bf16 q (bf16 or e4m3 K/V), d = 128, Hq/Hkv <= 16, G * Hq/Hkv <= 256,
+                              scale > 0 and, for a paged store, pages of at least 32 rows.  Everything
+                              else -- fp32, d = 64, other head ratios or scales, smaller pages -- runs on
+                              SIMPLE, which is an order of magnitude slower on large batches (1.04 ms
+                              against 0.11 ms on the 7B-shaped benchmark): rl_decode_attn_plan tells which
+                              one a descriptor gets. */
   RLDA_ALGO_SIMPLE = 1,    /* one wavefront per (sequence, query head), no sharing, no split */
   RLDA_ALGO_SHARED = 2     /* force the shared-prefix path; RLDA_ERR_UNSUPPORTED if not possible */
 } rlda_algo;
@@ -198,7 +209,7 @@ int rl_decode_attn_version(void);
  * Key n of sequence b's suffix is row n % page_size of page
  * block_table[b, n / page_size].  A page holds all KV heads:
  * k_pages / v_pages are [n_pages, Hkv, page_size, d].  page_size is a power of
- * two >= 32.  Table entries at or beyond ceil(suffix_lens[b] / page_size) are
+ * two (below 32 rows the call runs on RLDA_ALGO_SIMPLE).  Table entries at or beyond ceil(suffix_lens[b] / page_size) are
  * never read as page ids of live keys and may hold anything; entries that are
  * used are clamped to [0, n_pages) (a wrong id gives a wrong result, never an
  * out-of-pool access).  suffix_lens are clamped to [0, max_pages * page_size].
@@ -218,7 +229,7 @@ typedef struct {
   int32_t  P, G;
   int32_t  Hq, Hkv, d;
   int32_t  Lp_cap;             /* row capacity of the prefix buffers                             */
-  int32_t  page_size;          /* rows per page: 32, 64, 128, ... (power of two)                 */
+  int32_t  page_size;          /* rows per page, a power of two (>= 32 for the shared-prefix path) */
   int32_t  max_pages;          /* columns of block_table (>= 0)                                  */
   int32_t  n_pages;            /* pages in the pool (>= 1 if max_pages > 0)                      */
   float    scale;

@@ -24,7 +24,10 @@
  *   kl[b]          = sum_i p_i (ln p_i - ln r_i),   r = softmax(w[b,:])
  * y_b = token_ids[b].  A negative id marks an ignored position (logprob and
  * ref_logprob 0); an id >= vocab gives NaN there; no logit is read out of
- * range in either case.  Arithmetic is fp32 (inputs fp32 or bf16).
+ * range in either case.  A logit of -inf is a masked token (p_i = 0, nothing
+ * added to the sums); a NaN logit is read as a masked token too, it does not
+ * propagate.  inv_temperature must be positive and finite (else -1).
+ * Arithmetic is fp32 (inputs fp32 or bf16).
  */
 #ifndef RL_TOKEN_LOGPROB_H
 #define RL_TOKEN_LOGPROB_H

@@ -33,7 +33,7 @@ int to_problem(const rlda_paged_desc* ds, Problem& pb) {
   if (!ds) return RLDA_ERR_INVALID;
   if (ds->struct_size != sizeof(rlda_paged_desc)) return RLDA_ERR_STRUCT_SIZE;
   if (ds->max_pages < 0 || ds->n_pages < 0 || ds->page_size <= 0) return RLDA_ERR_INVALID;
-  if (ds->page_size < 32 || (ds->page_size & (ds->page_size - 1))) return RLDA_ERR_UNSUPPORTED;
+  if (ds->page_size & (ds->page_size - 1)) return RLDA_ERR_UNSUPPORTED;   // below 32 rows: the simple kernel only
   if ((int64_t)ds->max_pages * ds->page_size > (int64_t)1 << 30) return RLDA_ERR_UNSUPPORTED;
   if (ds->max_pages > 0 && ds->n_pages < 1) return RLDA_ERR_INVALID;
   pb = Problem{};
@@ -42,6 +42,7 @@ int to_problem(const rlda_paged_desc* ds, Problem& pb) {
   pb.Lp_cap = ds->Lp_cap; pb.Ls_cap = ds->max_pages * ds->page_size; pb.scale = ds->scale;
   pb.q = ds->q; pb.k_prefix = ds->k_prefix; pb.v_prefix = ds->v_prefix; pb.prefix_lens = ds->prefix_lens;
   pb.k_suffix = ds->k_pages; pb.v_suffix = ds->v_pages; pb.suffix_lens = ds->suffix_lens;
+  pb.paged = true;
   pb.block_table = ds->block_table;
   pb.page_shift = __builtin_ctz((unsigned)ds->page_size);
   pb.max_pages = ds->max_pages; pb.n_pages = ds->n_pages;

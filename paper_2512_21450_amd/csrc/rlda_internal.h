@@ -21,6 +21,7 @@ struct Problem {
   const void* k_prefix; const void* v_prefix; const int32_t* prefix_lens;
   const void* k_suffix; const void* v_suffix;   // [B, Hkv, Ls_cap, d], or the pools [n_pages, Hkv, page_size, d]
   const int32_t* suffix_lens;
+  bool paged;                     // the suffix store is a page pool with a block table (rlda_paged_desc)
   const int32_t* block_table;     // null: contiguous suffix store
   int page_shift;                 // log2(page_size)
   int max_pages, n_pages;

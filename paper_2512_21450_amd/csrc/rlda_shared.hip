@@ -1385,7 +1385,9 @@ bool shared_supported(const Problem& ds) {
   // The scan of tile counts lives in LDS.  A batch with more prompts and sequences than it holds is run as
   // several launches over whole prompts (max_prompts_per_launch); the tree form has to fit as it is.
   if (ds.n_levels > 0 ? E + B + 1 > MAX_SCAN : ds.G + 2 > MAX_SCAN) return false;
-  int64_t ptiles = (int64_t)ds.P * ds.Hkv * ceil_div(ds.Lp_cap, TK);
+  if (ds.paged && ds.page_shift < 5) return false;                      // a 32-key tile must not straddle pages
+  const int NHp = row_parts(r * max_group(ds));                         // prefix units per (prompt, KV head)
+  int64_t ptiles = (int64_t)ds.P * ds.Hkv * NHp * ceil_div(ds.Lp_cap, TK);
   int64_t pcap = ds.Lp_cap;
   if (ds.n_levels > 0) {
     // the tree form: bf16 stores, contiguous suffix, one row part (the largest group has at most 64 query rows per KV head)
@@ -1397,6 +1399,10 @@ bool shared_supported(const Problem& ds) {
     }
   }
   if (ptiles > MAX_LINE || B * ds.Hkv * ceil_div(ds.Ls_cap, TK) > MAX_LINE) return false;       // 32-bit tile arithmetic
+  // partial slots are indexed in 32 bits, also times two in the combine kernels
+  const int64_t slot_rows = NHp > 1 ? 64 : (int64_t)r * max_group(ds);
+  if ((E * ds.Hkv * NHp + N_WG) * slot_rows * 2 >= (int64_t)1 << 31 ||
+      (B * ds.Hkv + (int64_t)WG_WAVES * N_WG) * r * 2 >= (int64_t)1 << 31) return false;
   if (pcap * ROWB >= (int64_t)1 << 31 || (int64_t)ds.Ls_cap * ROWB >= (int64_t)1 << 31) return false;
   return true;
 }

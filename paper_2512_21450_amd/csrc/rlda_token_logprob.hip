@@ -140,14 +140,15 @@ __device__ __forceinline__ void finish_row(const Params& P, long long row, const
   const float lse = dead ? -INFINITY : lse2 * LN2;
   if (P.lse) P.lse[row] = lse;
   if (P.entropy) P.entropy[row] = dead ? NAN : (lse2 - mean_a) * LN2;
-  if (P.logprob) P.logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (a_y <= MASKED ? -INFINITY : (a_y - lse2) * LN2));
+  // !(x > MASKED): masked, also when the sampled token's logit is NaN (read as masked like every NaN logit)
+  if (P.logprob) P.logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (!(a_y > MASKED) ? -INFINITY : (a_y - lse2) * LN2));
   if (REF) {
     const float lse_r2 = A.mr + __log2f(A.sr);
     float mean_b = A.u / A.s;                               // sum_i p_i b_i; a masked reference logit under p > 0
     if (mean_b < -1e6f) mean_b = -INFINITY;                 // drags it towards MASKED: the KL is infinite
     if (P.kl) P.kl[row] = dead ? NAN : (mean_a - mean_b - lse2 + lse_r2) * LN2;
     if (P.ref_logprob)
-      P.ref_logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (b_y <= MASKED ? -INFINITY : (b_y - lse_r2) * LN2));
+      P.ref_logprob[row] = y < 0 ? 0.f : (y >= P.V ? NAN : (!(b_y > MASKED) ? -INFINITY : (b_y - lse_r2) * LN2));
   }
 }
 
@@ -242,6 +243,7 @@ int check(const rl_token_logprob_desc* d) {
   if (!d) return -1;
   if (d->struct_size != sizeof(rl_token_logprob_desc)) return -4;
   if (d->n_rows < 0 || d->vocab < 1 || d->row_stride < 0) return -1;
+  if (!(d->inv_temperature > 0.f) || d->inv_temperature > 3.0e38f) return -1;   // masked (-inf) logits must stay -inf after scaling
   if (d->dtype != 0 && d->dtype != 1) return -2;
   const int vn = d->dtype == 0 ? 4 : 8;
   if (d->row_stride < d->vocab || d->row_stride % vn != 0) return -2;

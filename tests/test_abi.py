@@ -154,7 +154,6 @@ def test_paged_descriptor_layout_matches_the_header():
 
 @pytest.mark.parametrize("kw,code", [
     (dict(page_size=48), B.RLDA_ERR_UNSUPPORTED),       # not a power of two
-    (dict(page_size=16), B.RLDA_ERR_UNSUPPORTED),       # smaller than a key tile
     (dict(page_size=0), B.RLDA_ERR_INVALID),
     (dict(max_pages=-1), B.RLDA_ERR_INVALID),
     (dict(n_pages=0), B.RLDA_ERR_INVALID),              # a table with columns needs a pool
@@ -167,6 +166,15 @@ def test_paged_shape_errors(kw, code):
     assert B.rl_decode_attn_paged_plan(ds) == code
     assert B.rl_decode_attn_paged_raw(ds) == code
     assert B.rl_decode_attn_paged_workspace_bytes(ds) == 0
+
+
+def test_small_pages_plan_onto_the_simple_kernel():
+    # a page shorter than a 32-key tile: the shared-prefix path cannot take it, the simple kernel resolves pages key by key
+    for ps in (1, 8, 16):
+        assert B.rl_decode_attn_paged_plan(good_paged(page_size=ps)) == B.RLDA_ALGO_SIMPLE
+        assert B.rl_decode_attn_paged_workspace_bytes(good_paged(page_size=ps)) == 0
+        assert B.rl_decode_attn_paged_plan(good_paged(page_size=ps, algo=B.RLDA_ALGO_SHARED)) == B.RLDA_ERR_UNSUPPORTED
+    assert B.rl_decode_attn_paged_plan(good_paged(page_size=32)) == B.RLDA_ALGO_SHARED
 
 
 def test_paged_plan_workspace_and_pointer_checks():
@@ -208,6 +216,14 @@ def test_token_logprob_shape_errors(kw, code):
     ds = good_tl(**kw)
     assert B.rl_token_logprob_raw(ds) == code
     assert B.rl_token_logprob_workspace_bytes(ds) == 0
+
+
+def test_token_logprob_temperature_must_be_positive_and_finite():
+    for t in (0.0, -1.0, float("nan"), float("inf")):
+        ds = good_tl()
+        ds.inv_temperature = t
+        assert B.rl_token_logprob_raw(ds) == -1
+        assert B.rl_token_logprob_workspace_bytes(ds) == 0
 
 
 def test_token_logprob_pointer_and_workspace_checks():

@@ -34,7 +34,7 @@ def test_full_size_configs_paged(B, name, ps):
     check(y, w.dtype, w.scale, w.G, what=f"paged {name}")
 
 
-@pytest.mark.parametrize("ps", [32, 64, 128, 256, 512])
+@pytest.mark.parametrize("ps", [16, 32, 64, 128, 256, 512])     # 16 rows: shorter than a key tile, the simple kernel's
 @pytest.mark.parametrize("dtype,d,algo", [("bf16", 128, "auto"), ("bf16", 128, "simple"), ("f32", 64, "auto")])
 def test_page_sizes_on_both_kernel_families(B, ps, dtype, d, algo):
     x = util.random_case(100 + ps, 3, 4, 8, 2, d, 150, 700, dtype)

@@ -30,6 +30,11 @@ def dev(a):
     return torch.from_numpy(a).cuda()
 
 
+def torch_finite(t):
+    import torch
+    return bool(torch.isfinite(t).all())
+
+
 def check(B, x, invT=1.0, what="", stride=None):
     import torch
     lg, rf = dev(x["logits"]), (dev(x["ref_logits"]) if "ref_logits" in x else None)
@@ -87,6 +92,17 @@ def test_ignored_and_out_of_range_ids_and_masked_logits(B):
     x["ref_logits"][2, 100:9000] = -np.inf                   # reference masked alike on row 2: finite KL there
     got = check(B, x, what="ids and masks", stride=20012)
     assert got["logprob"][0] == 0 and got["logprob"][5] == 0 and got["ref_logprob"][0] == 0
+
+
+def test_nan_logits_count_as_masked_tokens(B):
+    # the stated reading: a NaN logit is a masked token and does not propagate; the oracle reads it the same way
+    x = wl.make_logits(9, 20011, seed=10, dtype="f32", with_ref=True)
+    x["logits"][:, [0, 77, 12000, 20010]] = np.nan
+    x["logits"][2, 300:9000] = np.nan
+    x["ref_logits"][:, [5, 77]] = np.nan
+    x["token_ids"][1] = 77                                   # a NaN logit was "sampled": log-prob -inf
+    got = check(B, x, what="nan logits", stride=20012)
+    assert torch_finite(got["lse"]) and torch_finite(got["entropy"])
 
 
 def test_peaked_and_large_logits(B):
