@@ -307,14 +307,18 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
   const int n_cu = pairs_for(compute_units);
   const int B = P * G;
   if (rows_per_kv_group > MAX_GROUP_ROWS) return RLDA_ERR_INVALID;
-  const int HkvP = Hkv * row_parts(rows_per_kv_group);                  // prefix units per prompt: (KV head, row part)
+  // prefix units per prompt on the line, (KV head, line part); with SM = 2 twin pairs walk it, for row halves
+  // 2 * part + side.  Runs and parts are reported with j = head * row_parts + half.
+  const int NHl = line_parts(rows_per_kv_group, n_cu), SM = side_parts(rows_per_kv_group, n_cu);
+  const int HkvP = Hkv * NHl;
+  auto unit_j = [&](int jl, int side) { return (jl / NHl) * NHl * SM + (jl % NHl) * SM + side; };
   std::vector<int> X(P + B + 2, 0);
   auto tp = [&](int p) { return ceil_div(clampi(prefix_lens[p], 0, Lp_cap), TK); };
   auto ts = [&](int b) { return ceil_div(clampi(suffix_lens[b], 0, Ls_cap), TK); };
   for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
   for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
   const int cumP = X[P];
-  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, n_cu);
+  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, n_cu, SM == 2);
   int64_t nr = 0, np = 0;
   auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
     if (runs && nr < runs_cap) {
@@ -331,7 +335,10 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
       int p, j, t;
       locate(X.data(), P, HkvP, ilo, p, j, t);
       for_each_run(ilo, ihi, P, HkvP, p, j, t, tp,
-                   [&](int pp, int jj, int t0, int n) { put_run(0, pp, jj, t0, n, w, -1, pp * HkvP + jj + wg_rank(sc, w)); });
+                   [&](int pp, int jj, int t0, int n) {
+                     const int side = prefix_side(sc, w & (n_cu - 1));
+                     put_run(0, pp, unit_j(jj, side), t0, n, w, -1, (pp * HkvP + jj + wg_prefix_rank(sc, w)) * SM + side);
+                   });
     }
     for (int v = 0; v < WG_WAVES; ++v) {
       int ka, kb;
@@ -353,9 +360,11 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
   };
   for (int p = 0; p < P; ++p)                    // the combine kernel's enumeration
     for (int j = 0; j < HkvP; ++j)
-      for_each_prefix_part(sc, X.data(), HkvP, p, j, [&](int rank) {
-        put_part(0, p, j, rank % 2 ? n_cu + rank / 2 : rank / 2, -1, p * HkvP + j + rank);
-      });
+      for (int side = 0; side < SM; ++side)
+        for_each_prefix_part(sc, X.data(), HkvP, p, j, side, [&](int rank) {
+          const int c = share_pair(sc, rank / 2, side);
+          put_part(0, p, unit_j(j, side), rank % 2 ? n_cu + c : c, -1, (p * HkvP + j + rank) * SM + side);
+        });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)
       for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j, [&](int rank, int v) {

@@ -23,10 +23,19 @@
 // over the wavefronts) and then cuts its suffix tiles into WG_WAVES consecutive
 // runs, one per wavefront.
 //
+// A KV group of more than 64 query rows ("dual" partition) is handled in row halves of 64
+// by twin pairs: pairs c and c ^ 8 run on the same die (workgroup i goes to die i % 8) and
+// walk the same share of the prefix line at the same time, one for the even half of the
+// rows and one for the odd half, so that a tile is fetched from memory once and the second
+// request finds it in the die's L2.  The line then has n_cu / 2 shares of twice the length;
+// with more than 128 rows it holds every (prompt, KV head) twice, once per pair of halves.
+// Everything else (the split inside a pair, the suffix line) is as above.
+//
 // Every maximal run of tiles of one unit inside one workgroup (prefix) or one
 // wavefront (suffix) yields one partial (o, lse); its slot is unit + (2c + [B])
 // (prefix) or unit + WG_WAVES*(2c + [B]) + wavefront (suffix), unique because
-// both terms are monotone along the line.  Nothing here depends on run-time timing, so
+// both terms are monotone along the line (dual: 2 * (line unit + 2q + [B]) + side with q the
+// share of the twins, for the same reason).  Nothing here depends on run-time timing, so
 // the split and hence the rounding order is the same on every call.
 #pragma once
 
@@ -61,24 +70,35 @@ struct Sched {
   int n_cu;     // workgroup pairs, a power of two
   int cu_sh;    // its logarithm
   bool heavy;   // the prefix tiles outweigh the suffix tiles: B workgroups share them, A takes no suffix
+  bool dual;    // twin pairs walk the same prefix tiles, for different row halves
+  int tb;       // dual: pairs c and c ^ (1 << tb) are twins
+  int psh;      // logarithm of the number of shares of the prefix line (cu_sh, dual: cu_sh - 1)
 };
 
 __host__ __device__ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// The R = G * Hq/Hkv query rows that share a prefix tile are handled in row parts of at most 64
-// rows (one 16-row block per wavefront): 1, 2 or 4 parts.
+// The R = G * Hq/Hkv query rows that share a prefix tile are handled in row parts ("halves") of at
+// most 64 rows (one 16-row block per wavefront): 1, 2 or 4 parts.  With several parts and at least
+// two pairs, twin pairs take one each (side_parts = 2) and the line holds line_parts units per
+// (prompt, KV head).
 constexpr int MAX_GROUP_ROWS = 256;
 __host__ __device__ inline int row_parts(int R) { return R > 128 ? 4 : (R > 64 ? 2 : 1); }
+__host__ __device__ inline int side_parts(int R, int n_cu) { return R > 64 && n_cu > 1 ? 2 : 1; }
+__host__ __device__ inline int line_parts(int R, int n_cu) { return row_parts(R) / side_parts(R, n_cu); }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// wP is the weight for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead
-__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu) {
+// wP is the weight for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead.
+// NPT counts the tiles of the prefix line (in a dual partition every one is walked twice; n_cu > 1 then).
+__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu, bool dual = false) {
   Sched s;
-  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_cu = n_cu;
+  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_cu = n_cu; s.dual = dual;
   s.cu_sh = 0;
   while ((1 << s.cu_sh) < n_cu) ++s.cu_sh;
-  s.heavy = wP * NPT > wS * NST;               // lines are at most MAX_LINE tiles: no overflow
-  s.wP = !s.heavy && NPT + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : wP;
+  s.tb = s.cu_sh > 3 ? 3 : (s.cu_sh > 0 ? s.cu_sh - 1 : 0);   // twins on one die: the die is c % 8 (fewer than 16 pairs: one die)
+  s.psh = dual ? s.cu_sh - 1 : s.cu_sh;
+  const int walked = dual ? 2 * NPT : NPT;     // lines are at most MAX_LINE tiles: no overflow
+  s.heavy = wP * walked > wS * NST;
+  s.wP = !s.heavy && walked + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : wP;
   return s;
 }
 
@@ -93,11 +113,21 @@ __host__ __device__ inline int share_owner(int N, int i, int cu_sh) {
   return (int)(((((unsigned)(i + 1)) << cu_sh) + (unsigned)N - 1u) / (unsigned)N) - 1;
 }
 
+// share of the prefix line that pair c walks, the row half it walks it for (dual), and the pair of a share and side
+__host__ __device__ inline int prefix_share(const Sched& s, int c) {
+  return s.dual ? ((c >> (s.tb + 1)) << s.tb) | (c & ((1 << s.tb) - 1)) : c;
+}
+__host__ __device__ inline int prefix_side(const Sched& s, int c) { return s.dual ? (c >> s.tb) & 1 : 0; }
+__host__ __device__ inline int share_pair(const Sched& s, int q, int side) {
+  return s.dual ? ((q >> s.tb) << (s.tb + 1)) | (side << s.tb) | (q & ((1 << s.tb) - 1)) : q;
+}
+
 // prefix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  B gets some only
 // in a prefix-heavy batch, and then as many as even out the pair.
 __host__ __device__ inline void pair_prefix_range(const Sched& s, int c, int& lo, int& mid, int& hi) {
-  lo = share(s.NPT, c, s.cu_sh);
-  hi = share(s.NPT, c + 1, s.cu_sh);
+  const int q = prefix_share(s, c);
+  lo = share(s.NPT, q, s.psh);
+  hi = share(s.NPT, q + 1, s.psh);
   mid = hi;
   if (s.heavy) {
     const int ns = share(s.NST, c + 1, s.cu_sh) - share(s.NST, c, s.cu_sh);
@@ -109,7 +139,7 @@ __host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, 
   pair_prefix_range(s, w & (s.n_cu - 1), a, m, b);
   if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
 }
-__host__ __device__ inline int prefix_tile_pair(const Sched& s, int i) { return share_owner(s.NPT, i, s.cu_sh); }
+__host__ __device__ inline int prefix_tile_share(const Sched& s, int i) { return share_owner(s.NPT, i, s.psh); }
 
 // suffix tiles of pair c: [lo, hi), of which A takes [lo, mid) and B [mid, hi).  A gets some only
 // in a suffix-heavy batch, and then as many as even out the pair.
@@ -118,7 +148,8 @@ __host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo
   hi = share(s.NST, c + 1, s.cu_sh);
   mid = lo;
   if (!s.heavy) {
-    const int np = share(s.NPT, c + 1, s.cu_sh) - share(s.NPT, c, s.cu_sh);
+    const int q = prefix_share(s, c);
+    const int np = share(s.NPT, q + 1, s.psh) - share(s.NPT, q, s.psh);
     mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
   }
 }
@@ -139,8 +170,12 @@ __host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {
   const int q = ceil_div(hi - lo, WG_WAVES);
   return (k - lo) / q;
 }
-// slot term of workgroup w on either line (A and B of a pair are neighbours there, A first)
+// slot term of workgroup w on the suffix line (A and B of a pair are neighbours there, A first) and on the
+// prefix line (the same, by share)
 __host__ __device__ inline int wg_rank(const Sched& s, int w) { return w < s.n_cu ? 2 * w : 2 * (w - s.n_cu) + 1; }
+__host__ __device__ inline int wg_prefix_rank(const Sched& s, int w) {
+  return 2 * prefix_share(s, w & (s.n_cu - 1)) + (w < s.n_cu ? 0 : 1);
+}
 
 // ---- walking the line -------------------------------------------------------------------
 // X is the exclusive scan of per-head tile counts over `n` prompts (or sequences); every
@@ -175,17 +210,19 @@ __host__ __device__ inline void for_each_run(int lo, int hi, int n, int Hkv, int
   }
 }
 
-// Workgroups (by rank) holding a partial of prefix unit (p, j): fn(rank) in line order.  Xp = scan over prompts.
+// Workgroups (by prefix rank) holding a partial of unit (p, j) of the prefix line for row half `side` (0 unless
+// dual): fn(rank) in line order.  Xp = scan over prompts.
 template <class Fn>
-__host__ __device__ inline void for_each_prefix_part(const Sched& s, const int* Xp, int Hkv, int p, int j, Fn fn) {
+__host__ __device__ inline void for_each_prefix_part(const Sched& s, const int* Xp, int Hkv, int p, int j, int side,
+                                                     Fn fn) {
   const int T = Xp[p + 1] - Xp[p];
   if (T <= 0) return;
   const int is = Xp[p] * Hkv + j * T, ie = is + T;
-  for (int c = prefix_tile_pair(s, is); c <= prefix_tile_pair(s, ie - 1); ++c) {
-    int lo, mid, hi;                             // with fewer tiles than pairs some own nothing
-    pair_prefix_range(s, c, lo, mid, hi);
-    if ((lo > is ? lo : is) < (mid < ie ? mid : ie)) fn(2 * c);
-    if (s.heavy && (mid > is ? mid : is) < (hi < ie ? hi : ie)) fn(2 * c + 1);
+  for (int q = prefix_tile_share(s, is); q <= prefix_tile_share(s, ie - 1); ++q) {
+    int lo, mid, hi;                             // with fewer tiles than shares some hold nothing
+    pair_prefix_range(s, share_pair(s, q, side), lo, mid, hi);
+    if ((lo > is ? lo : is) < (mid < ie ? mid : ie)) fn(2 * q);
+    if (s.heavy && (mid > is ? mid : is) < (hi < ie ? hi : ie)) fn(2 * q + 1);
   }
 }
 

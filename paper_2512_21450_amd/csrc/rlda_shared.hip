@@ -71,8 +71,9 @@ struct SharedParams {
   // The R = G * r query rows of a KV group are handled in NH = 1, 2 or 4 row parts of at most 64
   // rows (NH = 2^NHs, more than one when R > 64): a prefix unit is (prompt, KV head, part), numbered
   // jp = j * NH + part, so that a wavefront never carries more than one 16-row block.
-  // HkvP = Hkv * NH units per prompt; a prefix partial slot holds RS rows.
-  int NH, NHs, HkvP, RS;
+  // The prefix line holds HkvP = Hkv * NH units per prompt (NH = 1 << NHs); with SM = 2 each is walked by twin
+  // pairs, for row halves 2 * (unit % NH) and 2 * (unit % NH) + 1.  A prefix partial slot holds RS rows.
+  int NH, NHs, HkvP, RS, SM;
   float c;                // scale * log2(e): scores are kept in base 2
   // extended form only (kernels instantiated with EXT = true):
   const int32_t* table;   // [B, max_pages] page ids when ks / vs are page pools [n_pages, Hkv, page, D], else null
@@ -498,7 +499,7 @@ __device__ __forceinline__ void cur_step(Cur& c, int by, LenOf len_of, int n, in
 // TREE: the units are segments of several levels, each with its own store, capacity and group size.
 struct PrefixUnit { const char* k; const char* v; int cap, R, b0; };   // stores of the segment (all KV heads), rows, first sequence
 template <int NRB, int NT, bool EXT, bool F8, bool REREAD, bool TREE>
-__device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int tid) {
+__device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, Cur cur, int n, int rank, int side, int tid) {
   auto len_of = [&](int p) { return plen_of<EXT, TREE>(P, p); };
   const int lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   using St = Stage<F8>;
@@ -507,7 +508,10 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
   const int rb = wv & (NRB - 1), part = wv / NRB, s_lo = part * NRB;
   const int rowbase = 16 * NT * rb;                         // inside the unit's row half
   const int lrow = St::lrow(lane), chunk = St::chunk(lane);
-  auto half_of = [&](const Cur& c) { return c.j & (P.NH - 1); };
+  auto half_of = [&](const Cur& c) {                        // row half of the unit that this workgroup computes
+    if constexpr (REREAD) return (c.j & (P.NH - 1)) * P.SM + side;
+    else return c.j & (P.NH - 1);
+  };
   auto head_of = [&](const Cur& c) { return c.j >> P.NHs; };
   // where the K and V rows of unit c start in their store, its query rows and its first sequence
   auto unit_of = [&](const Cur& c) {
@@ -520,7 +524,7 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
       return PrefixUnit{P.kp + off, P.vp + off, P.Lp_cap, P.R, c.u * P.G};
     }
   };
-  constexpr bool reread = REREAD;                           // every prefix tile is read once per row part: keep it cached
+  constexpr bool reread = REREAD;                           // the twin pair reads the same tile: keep it cached
   char* mine = lds + wv * STAGE_B;
 
   constexpr bool QPRE = NT == 1;                            // query rows of the next unit are prefetched (one block per wavefront)
@@ -659,7 +663,8 @@ __device__ __forceinline__ void prefix_stream(const SharedParams& P, char* lds, 
         lds_barrier();                                      // parked state is dead before tiles are stored again
       }
       if (active && part == 0)
-        write_partial<NT>(st, P.po, P.pl, cur.u * P.HkvP + cur.j + rank, P.RS, rowbase, lane,
+        write_partial<NT>(st, P.po, P.pl, REREAD ? (cur.u * P.HkvP + cur.j + rank) * P.SM + side : cur.u * P.HkvP + cur.j + rank,
+                          P.RS, rowbase, lane,
                           F8 && P.vscale ? P.vscale[head_of(cur)] : 1.f);
     }
     fresh = next_fresh; cur = nxt; rem = rem2; gs = ngs;
@@ -747,7 +752,7 @@ __device__ __forceinline__ void suffix_stream(const SharedParams& P, char* wlds,
   }
 }
 
-template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false, bool TREE = false>   // REREAD: KV groups of several row parts (NRB = 4)
+template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false, bool TREE = false>   // REREAD: KV groups of several row halves (NRB = 4), dual partition
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
@@ -782,7 +787,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, REREAD && P.SM == 2);
   if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
@@ -803,7 +808,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   if (ilo < ihi) {
     Cur c{pp, pj, pt, 0, 0};
     cur_load(c, [&](int p) { return plen_of<EXT, TREE>(P, p); });
-    prefix_stream<NRB, NT, EXT, F8, REREAD, TREE>(P, lds, c, ihi - ilo, wg_rank(sc, w), tid);
+    prefix_stream<NRB, NT, EXT, F8, REREAD, TREE>(P, lds, c, ihi - ilo, wg_prefix_rank(sc, w),
+                                                  REREAD ? prefix_side(sc, w & (P.n_cu - 1)) : 0, tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
@@ -818,7 +824,8 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
 }
 
 // ---- combine: 32 lanes per (sequence, head) row.  Lane k of the row first owns part k: all lse
-// values of the row and the first eight parts' values are requested in one round trip; the lse
+// values of the row and the first sixteen parts' values are requested in one round trip (rows of a
+// small batch are cut into that many parts, and every further round trip shows in its step time); the lse
 // values become weights with two 32-lane reductions; then every lane accumulates its 4 columns.  Parts are taken in line order, so the sum has one fixed order.
 template <bool EXT, bool TREE = false>
 __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
@@ -835,10 +842,10 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, P.SM == 2);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
-  const int half = P.NH > 1 ? grow >> 6 : 0;
-  const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
+  const int half = P.RS == 64 ? grow >> 6 : 0, prow = grow - 64 * half;   // row half, row inside it
+  const int jp = j * P.NH + (half >> (P.SM - 1)), side = half & (P.SM - 1);  // its unit on the line, which twin computes it
 
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float M = -INFINITY, Z = 0.f;                             // running max and sum over batches of 32 parts
@@ -850,15 +857,15 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
       for (int l = 0; l < MAX_LEVELS; ++l) {
         if (l < P.n_lev) {
           const int e = P.lev[l].first + b / P.lev[l].G, erow = (b % P.lev[l].G) * P.r + hi_;
-          for_each_prefix_part(sc, X, P.Hkv, e, j, [&](int c) {
+          for_each_prefix_part(sc, X, P.Hkv, e, j, 0, [&](int c) {
             if (n == base + sub) mine = 2 * ((e * P.Hkv + j + c) * P.RS + erow);
             ++n;
           });
         }
       }
     } else {
-      for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
-        if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
+      for_each_prefix_part(sc, X, P.HkvP, p, jp, side, [&](int c) {
+        if (n == base + sub) mine = 2 * (((p * P.HkvP + jp + c) * P.SM + side) * P.RS + prow);
         ++n;
       });
     }
@@ -868,10 +875,11 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
     });
     const int cnt = min(n - base, 32);
     if (cnt <= 0) break;
-    // the first 8 parts' values are requested together with the lse values (one round trip)
-    f16x4 v8[8];
+    // the first FIRST parts' values are requested together with the lse values (one round trip)
+    constexpr int FIRST = 16, NEXT = 8;
+    f16x4 v8[FIRST];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < FIRST; ++u) {
       const int id = __shfl(mine, min(u, cnt - 1), 32);
       v8[u] = *reinterpret_cast<const f16x4*>(reinterpret_cast<const char*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D) + coff);
     }
@@ -892,23 +900,23 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
     M = Mn;
     acc.x *= resc; acc.y *= resc; acc.z *= resc; acc.w *= resc;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
+    for (int u = 0; u < FIRST; ++u) {
       const float wk = u < cnt ? __shfl(wsc, min(u, cnt - 1), 32) : 0.f;
       acc.x = fmaf(wk, (float)v8[u][0], acc.x); acc.y = fmaf(wk, (float)v8[u][1], acc.y);
       acc.z = fmaf(wk, (float)v8[u][2], acc.z); acc.w = fmaf(wk, (float)v8[u][3], acc.w);
     }
-    for (int k0 = 8; k0 < cnt; k0 += 4) {
-      f16x4 v[4];
-      float wk[4];
+    for (int k0 = FIRST; k0 < cnt; k0 += NEXT) {
+      f16x4 v[NEXT];
+      float wk[NEXT];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < NEXT; ++u) {
         const int k = min(k0 + u, cnt - 1);
         const int id = __shfl(mine, k, 32);
         wk[u] = k0 + u < cnt ? __shfl(wsc, k, 32) : 0.f;
         v[u] = *reinterpret_cast<const f16x4*>(reinterpret_cast<const char*>((id & 1 ? P.so : P.po) + (size_t)(id >> 1) * D) + coff);
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < NEXT; ++u) {
         acc.x = fmaf(wk[u], (float)v[u][0], acc.x); acc.y = fmaf(wk[u], (float)v[u][1], acc.y);
         acc.z = fmaf(wk[u], (float)v[u][2], acc.z); acc.w = fmaf(wk[u], (float)v[u][3], acc.w);
       }
@@ -948,10 +956,10 @@ __global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P)
   const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, P.SM == 2);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
-  const int half = P.NH > 1 ? grow >> 6 : 0;
-  const int jp = j * P.NH + half, prow = grow - 64 * half;  // prefix unit of the row, row inside it
+  const int half = P.RS == 64 ? grow >> 6 : 0, prow = grow - 64 * half;   // row half, row inside it
+  const int jp = j * P.NH + (half >> (P.SM - 1)), side = half & (P.SM - 1);  // its unit on the line, which twin computes it
 
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float M = -INFINITY, Z = 0.f;                             // running max and sum over batches of 16 parts
@@ -961,8 +969,8 @@ __global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P)
   for (int base = 0;; base += 16) {
     // part `base + sub` of this row, as 2 * (row index in its partial array) + [suffix]
     int n = 0, mine = -1;
-    for_each_prefix_part(sc, X, P.HkvP, p, jp, [&](int c) {
-      if (n == base + sub) mine = 2 * ((p * P.HkvP + jp + c) * P.RS + prow);
+    for_each_prefix_part(sc, X, P.HkvP, p, jp, side, [&](int c) {
+      if (n == base + sub) mine = 2 * (((p * P.HkvP + jp + c) * P.SM + side) * P.RS + prow);
       ++n;
     });
     for_each_suffix_part(sc, X + P.P, cumP, P.Hkv, b, j, [&](int rank, int v) {
@@ -1483,11 +1491,31 @@ hipError_t launch_shared(const Problem& whole, hipStream_t stream, hipEvent_t mi
     }
   }
 
+  // workgroup pairs: by the compute-unit count of the device, looked up once
+  {
+    static std::mutex mu;
+    static int pairs[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    if (dev < 0 || dev >= 64 || pairs[dev] == 0) {
+      int cus = 0;
+      e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e != hipSuccess) return e;
+      if (cus < 1) return hipErrorInvalidDevice;
+      P.n_cu = pairs_for(cus);
+      if (dev >= 0 && dev < 64) pairs[dev] = P.n_cu;
+    } else {
+      P.n_cu = pairs[dev];
+    }
+  }
   // row halves of the KV group, and wavefronts per prefix tile (NRB 16-row blocks, a power of two)
-  P.NH = row_parts(P.R);
+  P.SM = side_parts(P.R, P.n_cu);
+  P.NH = line_parts(P.R, P.n_cu);
   P.NHs = P.NH == 4 ? 2 : P.NH - 1;
   P.HkvP = P.Hkv * P.NH;
-  P.RS = P.NH > 1 ? 16 * WG_WAVES : P.R;
+  P.RS = P.R > 64 ? 16 * WG_WAVES : P.R;
   int nrb = 1;
   while (16 * nrb < P.RS) nrb *= 2;
   P.table = ds.block_table; P.active = ds.seq_active;
@@ -1507,33 +1535,23 @@ hipError_t launch_shared(const Problem& whole, hipStream_t stream, hipEvent_t mi
   static const kern_t tree_kerns[3] = {partial_kernel<1, 1, false, false, false, true>, partial_kernel<2, 1, false, false, false, true>,
                                        partial_kernel<4, 1, false, false, false, true>};
   const kern_t kern = tree ? tree_kerns[nrb == 1 ? 0 : nrb == 2 ? 1 : 2]
-                    : P.NH > 1 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
+                    : P.R > 64 ? kerns[12 + (f8 ? 2 : 0) + (ext ? 1 : 0)]
                                : kerns[(f8 ? 6 : 0) + (ext ? 3 : 0) + (nrb == 1 ? 0 : nrb == 2 ? 1 : 2)];
-  // once per device: the compute-unit count decides the workgroup pairs; a kernel that uses more than 64 KB of
-  // LDS in total needs an opt-in
+  // once per device: a kernel that uses more than 64 KB of LDS in total needs an opt-in
   {
     static std::mutex mu;
     static bool done[64] = {};
-    static int pairs[64] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     std::lock_guard<std::mutex> lock(mu);
     if (dev < 0 || dev >= 64 || !done[dev]) {
-      int cus = 0;
-      e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-      if (e != hipSuccess) return e;
-      if (cus < 1) return hipErrorInvalidDevice;
-      if (dev >= 0 && dev < 64) pairs[dev] = pairs_for(cus);
-      P.n_cu = pairs_for(cus);
       for (int i = 0; i < 16 + 3; ++i) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(i < 16 ? kerns[i] : tree_kerns[i - 16]),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
       }
       if (dev >= 0 && dev < 64) done[dev] = true;
-    } else {
-      P.n_cu = pairs[dev];
     }
   }
   hipLaunchKernelGGL(kern, dim3(2 * P.n_cu), dim3(NTHREADS), LDS_BYTES, stream, P);
@@ -1546,7 +1564,7 @@ hipError_t launch_shared(const Problem& whole, hipStream_t stream, hipEvent_t mi
   const int rows = P.B * P.Hq;
   if (tree) {
     hipLaunchKernelGGL((combine_kernel<false, true>), dim3((rows + 7) / 8), dim3(256), 0, stream, P);
-  } else if ((int64_t)ds.P * P.HkvP >= COMBINE16_MIN_UNITS) {
+  } else if ((int64_t)ds.P * P.HkvP * P.SM >= COMBINE16_MIN_UNITS) {
     if (ext) hipLaunchKernelGGL(combine16_kernel<true>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
     else     hipLaunchKernelGGL(combine16_kernel<false>, dim3((rows + 15) / 16), dim3(256), 0, stream, P);
   } else {

@@ -43,7 +43,8 @@ def partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8, cus=256):
 
 
 def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8, cus=256):
-    """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half).
+    """R: query rows per KV group; above 64 the prefix units are (prompt, KV head, row half), and twin pairs
+    (c and c ^ 8, on one die) walk the same tiles, one for the even row half and one for the odd one.
     cus: compute units of the device the partition is made for."""
     runs, parts = partition(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R, cus)
     NC = _pairs(cus)                              # workgroup pairs
@@ -79,12 +80,28 @@ def check(P, G, Hkv, Lp_cap, Ls_cap, plens, slens, R=8, cus=256):
     # balance: the two workgroups of a pair (w and 256 + w share a compute unit) together hold
     # an equal share of the prefix tiles and of the suffix tiles, up to rounding
     npt, nst = int(tp.sum()) * HkvP, int(ts.sum()) * Hkv
+    dual = R > 64 and NC > 1
     for kind, total in ((0, npt), (1, nst)):
         load = np.zeros(NC, np.int64)
         rk = runs[runs[:, 0] == kind]
         np.add.at(load, rk[:, 5] % NC, rk[:, 4])
         assert load.sum() == total
-        assert load.max() <= -(-total // NC) and load.min() >= total // NC
+        if dual and kind == 0:                    # twins hold equal shares of the line of half the units
+            assert (total // 2) // (NC // 2) <= load.min() and load.max() <= -(-(total // 2) // (NC // 2))
+        else:
+            assert load.max() <= -(-total // NC) and load.min() >= total // NC
+    if dual:
+        # twin pairs walk the same prefix tiles (the split inside a pair may differ by the pairs' suffix shares),
+        # for row halves 2k (the pair without the twin bit) and 2k + 1
+        tb = min(3, NC.bit_length() - 2)
+        pre = runs[runs[:, 0] == 0]
+        tiles = {0: {}, 1: {}}
+        for _, major, j, t0, n, w, _, _ in pre:
+            side = ((w % NC) >> tb) & 1
+            assert j % 2 == side
+            share = (w % NC) & ~(1 << tb)
+            tiles[side].setdefault(share, set()).update((major, j - side, t) for t in range(t0, t0 + n))
+        assert tiles[0] == tiles[1]
     # inside a pair the heavier line is shared: the second workgroup has prefix tiles only if the first
     # has no suffix tiles, and the two then differ by less than two tiles' weight
     WP, WS = (14 if npt + nst < 16384 and 6 * npt <= 4 * nst else 6), 4   # small suffix-heavy batches weigh prefix tiles more
