@@ -32,8 +32,10 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # run, not measured in this one: reported only while the sources the kernel is built from still hash to
 # what the counters were taken on, null otherwise.
 PMC_TRAFFIC = {
-    "csrc_sha256": "",
-    "vlm7b": {"fetch_bytes": 0, "write_bytes": 0},
+    "csrc_sha256": "94efa54b794c593acca7badf995bce86ea6d573a9a4235d04bf255ca28ddd164",
+    "vlm7b": {"fetch_bytes": 623718046, "write_bytes": 9341542},
+    "agentic": {"fetch_bytes": 163229823, "write_bytes": 7260160},
+    "highbatch": {"fetch_bytes": 735240837, "write_bytes": 21287424},
 }
 
 OTHER_WORKLOADS = ("tiny", "vlm3b", "agentic", "highbatch")     # reported beside the default one, in short form
@@ -391,7 +393,8 @@ def main():
                            min(args.event_calls, 60), full=False)
             others[name] = {k: o[k] for k in ("ms_per_step", "value", "plan", "algorithmic_bytes", "whole_step_GBps",
                                               "whole_step_frac_of_hbm_peak", "whole_call_us_by_events",
-                                              "kernel_us_by_events", "kernel_frac_of_hbm_peak", "mean_suffix_len",
+                                              "kernel_us_by_events", "kernel_algorithmic_bytes", "kernel_frac_of_hbm_peak",
+                                              "traffic", "mean_suffix_len",
                                               "max_suffix_len", "mean_prefix_len", "parity")}
             torch.cuda.empty_cache()
 
