@@ -579,7 +579,7 @@ def bench_token_logprob(args, torch, B, wl, dev):
         step(i)
     torch.cuda.synchronize()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    every = max(args.event_every, 1)
+    every = 8                                               # two event records cost a few us: not on every step
     t0 = time.perf_counter()
     for i in range(args.steps):
         if i % every == 0:
