@@ -238,6 +238,7 @@ def run_decode(args, torch, B, wl, dev, wname, steps, warmup, event_calls, full)
         "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
         "mean_prefix_len": float(x["prefix_lens"].mean()),
         "parity": {"ok": parity_ok, "max_abs_err_out": err_o, "max_abs_err_lse": err_l, "rows": len(rows)},
+        "traffic": None if paged or kv8 else measured_traffic(w.name, plan),
     }
     if not full:
         del sets, base, descs, ws
@@ -307,7 +308,6 @@ def run_decode(args, torch, B, wl, dev, wname, steps, warmup, event_calls, full)
                      "mean_suffix_len": float(x["suffix_lens"].mean()), "max_suffix_len": int(x["suffix_lens"].max()),
                      "mean_prefix_len": float(x["prefix_lens"].mean())}
     res["dtype"] = w.dtype
-    res["traffic"] = None if paged or kv8 else measured_traffic(w.name, plan)
     return res
 
 

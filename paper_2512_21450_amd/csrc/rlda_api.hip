@@ -327,7 +327,8 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
     }
     ++nr;
   };
-  for (int w = 0; w < 2 * n_cu; ++w) {           // the partial kernel's walk
+  for (int x = 0; x < 2 * n_cu; ++x) {           // the partial kernel's walk; runs are reported by grid index
+    const int w = wg_name(sc, x);
     int ilo, ihi, klo, khi;
     wg_prefix_range(sc, w, ilo, ihi);
     wg_suffix_range(sc, w, klo, khi);
@@ -336,8 +337,8 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
       locate(X.data(), P, HkvP, ilo, p, j, t);
       for_each_run(ilo, ihi, P, HkvP, p, j, t, tp,
                    [&](int pp, int jj, int t0, int n) {
-                     const int side = prefix_side(sc, w & (n_cu - 1));
-                     put_run(0, pp, unit_j(jj, side), t0, n, w, -1, (pp * HkvP + jj + wg_prefix_rank(sc, w)) * SM + side);
+                     const int side = prefix_side(sc, wg_pair(sc, w));
+                     put_run(0, pp, unit_j(jj, side), t0, n, x, -1, (pp * HkvP + jj + wg_prefix_rank(sc, w)) * SM + side);
                    });
     }
     for (int v = 0; v < WG_WAVES; ++v) {
@@ -347,7 +348,7 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
       int b, j, t;
       locate(X.data() + P, B, Hkv, ka + cumP * Hkv, b, j, t);
       for_each_run(ka, kb, B, Hkv, b, j, t, ts, [&](int bb, int jj, int t0, int n) {
-        put_run(1, bb, jj, t0, n, w, v, bb * Hkv + jj + WG_WAVES * wg_rank(sc, w) + v);
+        put_run(1, bb, jj, t0, n, x, v, bb * Hkv + jj + WG_WAVES * wg_rank(sc, w) + v);
       });
     }
   }
@@ -363,12 +364,12 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
       for (int side = 0; side < SM; ++side)
         for_each_prefix_part(sc, X.data(), HkvP, p, j, side, [&](int rank) {
           const int c = share_pair(sc, rank / 2, side);
-          put_part(0, p, unit_j(j, side), rank % 2 ? n_cu + c : c, -1, (p * HkvP + j + rank) * SM + side);
+          put_part(0, p, unit_j(j, side), wg_grid_index(sc, c, rank % 2), -1, (p * HkvP + j + rank) * SM + side);
         });
   for (int b = 0; b < B; ++b)
     for (int j = 0; j < Hkv; ++j)
       for_each_suffix_part(sc, X.data() + P, cumP, Hkv, b, j, [&](int rank, int v) {
-        put_part(1, b, j, rank % 2 ? n_cu + rank / 2 : rank / 2, v, b * Hkv + j + WG_WAVES * rank + v);
+        put_part(1, b, j, wg_grid_index(sc, rank / 2, rank % 2), v, b * Hkv + j + WG_WAVES * rank + v);
       });
   *n_parts = np;
   return nr;

@@ -6,11 +6,15 @@
 // and owns ceil(Ls/TK) tiles.  Prefix tiles form one line (prompt-major, then KV
 // head, then tile), suffix tiles another (sequence-major, then KV head, then tile).
 //
-// The partial kernel runs 2 * n_cu workgroups, two per compute unit: workgroup
-// c ("A") and workgroup n_cu + c ("B") form pair c.  n_cu is the largest power of
+// The partial kernel runs 2 * n_launch workgroups, two per compute unit: workgroup
+// c ("A") and workgroup n_cu + c ("B") form pair c.  n_launch is the largest power of
 // two that is at most the device's compute-unit count and at most N_CU (256 on a
 // whole MI355X; 128, 64 or 32 when the device is one partition of it), so that
-// the share arithmetic is shifts.  Every pair gets the same
+// the share arithmetic is shifts, and n_cu = n_launch except for a small batch (fewer than
+// SPARSE_BATCH_TILES tiles), which is cut among n_cu = n_launch / 2 pairs, the first 2 * n_cu
+// workgroups, while the others stay idle: its wavefronts hold one or two tiles either way, but
+// its rows are then cut into half as many partial results, which is what the combine step's
+// time follows.  Every working pair gets the same
 // share of each line (position N*c/n_cu .. N*(c+1)/n_cu), so that every compute
 // unit carries the same mix of work and all finish together.  Inside a pair the
 // two workgroups are evened out by tile weight (a prefix tile costs wP, a suffix
@@ -62,12 +66,16 @@ constexpr int SUFFIX_WEIGHT = 4;  // ... relative to a suffix tile, when the bat
 // matrix work of all row blocks, so prefix tiles weigh more.
 constexpr int SMALL_BATCH_TILES = 16384;
 constexpr int PREFIX_WEIGHT_SMALL = 14;
+// A batch of fewer tiles than this (2 per wavefront of half the grid) works with half the pairs, down to 32
+// (not the dual partition of groups of more than 64 rows, which keeps the whole grid).
+constexpr int SPARSE_BATCH_TILES = 2048;
 
 struct Sched {
   int NPT;      // prefix tiles in total (all units)
   int NST;      // suffix tiles in total
   int wP, wS;   // tile weights
-  int n_cu;     // workgroup pairs, a power of two
+  int n_launch; // workgroup pairs launched, a power of two
+  int n_cu;     // workgroup pairs that get work (n_launch, or half of it for a small batch), a power of two
   int cu_sh;    // its logarithm
   bool heavy;   // the prefix tiles outweigh the suffix tiles: B workgroups share them, A takes no suffix
   bool dual;    // twin pairs walk the same prefix tiles, for different row halves
@@ -89,11 +97,11 @@ __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? l
 
 // wP is the weight for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead.
 // NPT counts the tiles of the prefix line (in a dual partition every one is walked twice; n_cu > 1 then).
-__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_cu, bool dual = false) {
+__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_launch, bool dual = false) {
   Sched s;
-  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_cu = n_cu; s.dual = dual;
-  s.cu_sh = 0;
-  while ((1 << s.cu_sh) < n_cu) ++s.cu_sh;
+  const int n_cu = !dual && NPT + NST < SPARSE_BATCH_TILES && n_launch >= 64 ? n_launch / 2 : n_launch;
+  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_launch = n_launch; s.n_cu = n_cu; s.dual = dual;
+  s.cu_sh = 31 - __builtin_clz((unsigned)n_cu);             // n_cu is a power of two >= 1
   s.tb = s.cu_sh > 3 ? 3 : (s.cu_sh > 0 ? s.cu_sh - 1 : 0);   // twins on one die: the die is c % 8 (fewer than 16 pairs: one die)
   s.psh = dual ? s.cu_sh - 1 : s.cu_sh;
   const int walked = dual ? 2 * NPT : NPT;     // lines are at most MAX_LINE tiles: no overflow
@@ -134,10 +142,22 @@ __host__ __device__ inline void pair_prefix_range(const Sched& s, int c, int& lo
     mid = hi - clampi((s.wP * (hi - lo) - s.wS * ns) / (2 * s.wP), 0, hi - lo);
   }
 }
+// Workgroups are named by w = c for the A and n_launch + c for the B of pair c; pairs from n_cu on are idle.
+// The grid's workgroup x takes the name wg_name(x): the first 2 * n_cu of the grid work (A of pair c is x = c, its
+// B is x = n_cu + c), the others take the name of an idle pair.
+__host__ __device__ inline int wg_name(const Sched& s, int x) {
+  if (x >= 2 * s.n_cu) return s.n_launch - 1;               // only when n_cu < n_launch: an idle pair
+  return (x & s.n_cu) ? s.n_launch + (x & (s.n_cu - 1)) : x;
+}
+__host__ __device__ inline int wg_grid_index(const Sched& s, int c, bool is_b) { return is_b ? s.n_cu + c : c; }
+__host__ __device__ inline int wg_pair(const Sched& s, int w) { return w & (s.n_launch - 1); }
+__host__ __device__ inline bool wg_is_b(const Sched& s, int w) { return w >= s.n_launch; }
 __host__ __device__ inline void wg_prefix_range(const Sched& s, int w, int& lo, int& hi) {
   int a, m, b;
-  pair_prefix_range(s, w & (s.n_cu - 1), a, m, b);
-  if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
+  const int c = wg_pair(s, w);
+  pair_prefix_range(s, c, a, m, b);
+  if (!wg_is_b(s, w)) { lo = a; hi = m; } else { lo = m; hi = b; }
+  if (c >= s.n_cu) lo = hi = 0;
 }
 __host__ __device__ inline int prefix_tile_share(const Sched& s, int i) { return share_owner(s.NPT, i, s.psh); }
 
@@ -155,8 +175,10 @@ __host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo
 }
 __host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
   int a, m, b;
-  pair_suffix_range(s, w & (s.n_cu - 1), a, m, b);
-  if (w < s.n_cu) { lo = a; hi = m; } else { lo = m; hi = b; }
+  const int c = wg_pair(s, w);
+  pair_suffix_range(s, c, a, m, b);
+  if (!wg_is_b(s, w)) { lo = a; hi = m; } else { lo = m; hi = b; }
+  if (c >= s.n_cu) lo = hi = 0;
 }
 __host__ __device__ inline int suffix_tile_pair(const Sched& s, int k) { return share_owner(s.NST, k, s.cu_sh); }
 
@@ -172,9 +194,9 @@ __host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {
 }
 // slot term of workgroup w on the suffix line (A and B of a pair are neighbours there, A first) and on the
 // prefix line (the same, by share)
-__host__ __device__ inline int wg_rank(const Sched& s, int w) { return w < s.n_cu ? 2 * w : 2 * (w - s.n_cu) + 1; }
+__host__ __device__ inline int wg_rank(const Sched& s, int w) { return 2 * wg_pair(s, w) + (wg_is_b(s, w) ? 1 : 0); }
 __host__ __device__ inline int wg_prefix_rank(const Sched& s, int w) {
-  return 2 * prefix_share(s, w & (s.n_cu - 1)) + (w < s.n_cu ? 0 : 1);
+  return 2 * prefix_share(s, wg_pair(s, w)) + (wg_is_b(s, w) ? 1 : 0);
 }
 
 // ---- walking the line -------------------------------------------------------------------

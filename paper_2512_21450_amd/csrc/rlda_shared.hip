@@ -756,7 +756,7 @@ template <int NRB, int NT, bool EXT, bool F8, bool REREAD = false, bool TREE = f
 __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams P) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ int wsum[WG_WAVES];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, w = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
 
   // ---- tile counts of all prompts and sequences, exclusive scan in LDS: every thread takes a
   // run of consecutive entries, the runs are chained by a wavefront scan and the wavefront totals
@@ -788,7 +788,9 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   __syncthreads();
   const int cumP = X[P.P];
   const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, REREAD && P.SM == 2);
-  if (w == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
+  if (blockIdx.x == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
+  // a small batch works with the first half of the grid (never in the dual partition)
+  const int w = REREAD ? (int)blockIdx.x : wg_name(sc, blockIdx.x);
 
   // ---- where this workgroup's prefix tiles and this wavefront's suffix tiles start
   int ilo, ihi, klo, khi, ka, kb;
@@ -809,7 +811,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
     Cur c{pp, pj, pt, 0, 0};
     cur_load(c, [&](int p) { return plen_of<EXT, TREE>(P, p); });
     prefix_stream<NRB, NT, EXT, F8, REREAD, TREE>(P, lds, c, ihi - ilo, wg_prefix_rank(sc, w),
-                                                  REREAD ? prefix_side(sc, w & (P.n_cu - 1)) : 0, tid);
+                                                  REREAD ? prefix_side(sc, wg_pair(sc, w)) : 0, tid);
   }
   if (ka < kb) {
     Cur c{sb, sj, st0, 0, 0};
