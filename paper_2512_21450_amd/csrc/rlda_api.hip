@@ -318,7 +318,7 @@ int64_t rl_decode_attn_debug_partition_on(int32_t compute_units, int32_t P, int3
   for (int i = 0; i < P; ++i) X[i + 1] = X[i] + tp(i);
   for (int i = 0; i < B; ++i) X[P + i + 1] = X[P + i] + ts(i);
   const int cumP = X[P];
-  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, n_cu, SM == 2);
+  const Sched sc = make_sched(cumP * HkvP, (X[P + B] - cumP) * Hkv, n_cu, SM == 2);
   int64_t nr = 0, np = 0;
   auto put_run = [&](int kind, int major, int j, int t0, int n, int w, int v, int slot) {
     if (runs && nr < runs_cap) {

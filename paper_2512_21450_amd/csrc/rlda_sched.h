@@ -73,7 +73,7 @@ constexpr int SPARSE_BATCH_TILES = 2048;
 struct Sched {
   int NPT;      // prefix tiles in total (all units)
   int NST;      // suffix tiles in total
-  int wP, wS;   // tile weights
+  int wP;       // weight of a prefix tile (a suffix tile weighs SUFFIX_WEIGHT)
   int n_launch; // workgroup pairs launched, a power of two
   int n_cu;     // workgroup pairs that get work (n_launch, or half of it for a small batch), a power of two
   int cu_sh;    // its logarithm
@@ -95,18 +95,18 @@ __host__ __device__ inline int side_parts(int R, int n_cu) { return R > 64 && n_
 __host__ __device__ inline int line_parts(int R, int n_cu) { return row_parts(R) / side_parts(R, n_cu); }
 __host__ __device__ inline int clampi(int v, int lo, int hi) { return v < lo ? lo : (v > hi ? hi : v); }
 
-// wP is the weight for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead.
+// The prefix weight is PREFIX_WEIGHT for a saturating batch; small suffix-heavy batches use PREFIX_WEIGHT_SMALL instead.
 // NPT counts the tiles of the prefix line (in a dual partition every one is walked twice; n_cu > 1 then).
-__host__ __device__ inline Sched make_sched(int NPT, int NST, int wP, int wS, int n_launch, bool dual = false) {
+__host__ __device__ inline Sched make_sched(int NPT, int NST, int n_launch, bool dual = false) {
   Sched s;
   const int n_cu = !dual && NPT + NST < SPARSE_BATCH_TILES && n_launch >= 64 ? n_launch / 2 : n_launch;
-  s.NPT = NPT; s.NST = NST; s.wS = wS; s.n_launch = n_launch; s.n_cu = n_cu; s.dual = dual;
+  s.NPT = NPT; s.NST = NST; s.n_launch = n_launch; s.n_cu = n_cu; s.dual = dual;
   s.cu_sh = 31 - __builtin_clz((unsigned)n_cu);             // n_cu is a power of two >= 1
   s.tb = s.cu_sh > 3 ? 3 : (s.cu_sh > 0 ? s.cu_sh - 1 : 0);   // twins on one die: the die is c % 8 (fewer than 16 pairs: one die)
   s.psh = dual ? s.cu_sh - 1 : s.cu_sh;
   const int walked = dual ? 2 * NPT : NPT;     // lines are at most MAX_LINE tiles: no overflow
-  s.heavy = wP * walked > wS * NST;
-  s.wP = !s.heavy && walked + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : wP;
+  s.heavy = PREFIX_WEIGHT * walked > SUFFIX_WEIGHT * NST;
+  s.wP = !s.heavy && walked + NST < SMALL_BATCH_TILES ? PREFIX_WEIGHT_SMALL : PREFIX_WEIGHT;
   return s;
 }
 
@@ -116,9 +116,18 @@ constexpr int MAX_LINE = (1 << 30) / N_CU;
 
 // pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles (cu_sh = log2 of the pair count)
 __host__ __device__ inline int share(int N, int c, int cu_sh) { return (int)(((unsigned)N * (unsigned)c) >> cu_sh); }
-// the pair that owns position i: the largest c with share(N, c) <= i
+// the pair that owns position i (0 <= i < N): the largest c with share(N, c) <= i, that is
+// ceil((i + 1) * 2^cu_sh / N) - 1.  A float quotient lands within one of it and two exact steps settle it
+// (an integer division costs the combine kernels, which ask four times per row, several times as much).
 __host__ __device__ inline int share_owner(int N, int i, int cu_sh) {
-  return (int)(((((unsigned)(i + 1)) << cu_sh) + (unsigned)N - 1u) / (unsigned)N) - 1;
+  const int last = (1 << cu_sh) - 1;
+  int c = (int)((float)(i + 1) * ((float)(1 << cu_sh) / (float)N));
+  c = c > last ? last : c;
+  if (share(N, c, cu_sh) > i) --c;
+  if (share(N, c, cu_sh) > i) --c;
+  if (c < last && share(N, c + 1, cu_sh) <= i) ++c;
+  if (c < last && share(N, c + 1, cu_sh) <= i) ++c;
+  return c;
 }
 
 // share of the prefix line that pair c walks, the row half it walks it for (dual), and the pair of a share and side
@@ -139,7 +148,7 @@ __host__ __device__ inline void pair_prefix_range(const Sched& s, int c, int& lo
   mid = hi;
   if (s.heavy) {
     const int ns = share(s.NST, c + 1, s.cu_sh) - share(s.NST, c, s.cu_sh);
-    mid = hi - clampi((s.wP * (hi - lo) - s.wS * ns) / (2 * s.wP), 0, hi - lo);
+    mid = hi - clampi((PREFIX_WEIGHT * (hi - lo) - SUFFIX_WEIGHT * ns) / (2 * PREFIX_WEIGHT), 0, hi - lo);   // wP = PREFIX_WEIGHT here
   }
 }
 // Workgroups are named by w = c for the A and n_launch + c for the B of pair c; pairs from n_cu on are idle.
@@ -170,7 +179,7 @@ __host__ __device__ inline void pair_suffix_range(const Sched& s, int c, int& lo
   if (!s.heavy) {
     const int q = prefix_share(s, c);
     const int np = share(s.NPT, q + 1, s.psh) - share(s.NPT, q, s.psh);
-    mid = lo + clampi((s.wS * (hi - lo) - s.wP * np) / (2 * s.wS), 0, hi - lo);
+    mid = lo + clampi((SUFFIX_WEIGHT * (hi - lo) - s.wP * np) / (2 * SUFFIX_WEIGHT), 0, hi - lo);
   }
 }
 __host__ __device__ inline void wg_suffix_range(const Sched& s, int w, int& lo, int& hi) {
@@ -188,9 +197,11 @@ __host__ __device__ inline void wave_suffix_range(int lo, int hi, int v, int& a,
   a = lo + v * q; if (a > hi) a = hi;
   b = a + q;      if (b > hi) b = hi;
 }
-__host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {
-  const int q = ceil_div(hi - lo, WG_WAVES);
-  return (k - lo) / q;
+__host__ __device__ inline int suffix_tile_wave(int lo, int hi, int k) {      // (k - lo) / q without the division
+  const int q = ceil_div(hi - lo, WG_WAVES), d = k - lo;
+  int v = 0;
+  for (int u = 1; u < WG_WAVES; ++u) v += d >= u * q ? 1 : 0;
+  return v;
 }
 // slot term of workgroup w on the suffix line (A and B of a pair are neighbours there, A first) and on the
 // prefix line (the same, by share)

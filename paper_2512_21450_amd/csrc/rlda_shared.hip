@@ -58,6 +58,21 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 struct TreeLevel { const char* k; const char* v; const int32_t* lens; int first, G, R, cap; };
 constexpr int MAX_LEVELS = RLDA_MAX_TREE_LEVELS;   // 4
 
+// n / d for 0 <= n < 2^31 as a multiplication: m = floor(2^k / d) + 1 with k = 31 + ceil(log2 d) (m fits 32 bits,
+// and m * d - 2^k <= d <= 2^(k - 31) makes the quotient exact).  The combine kernels split every row index three
+// times; a 32-bit integer division costs them about ten times this.
+struct FastDiv { uint32_t m; int k; };
+inline FastDiv make_fastdiv(int d) {
+  if (d < 1) d = 1;                                          // an empty batch launches nothing; keep the host safe
+  int l = 0;
+  while ((1 << l) < d) ++l;
+  FastDiv f;
+  f.k = 31 + l;
+  f.m = (uint32_t)(((uint64_t)1 << f.k) / (uint32_t)d + 1);
+  return f;
+}
+__device__ __forceinline__ int fast_div(int n, FastDiv f) { return (int)(((uint64_t)(uint32_t)n * f.m) >> f.k); }
+
 struct SharedParams {
   const char* q; const char* kp; const char* vp; const char* ks; const char* vs;
   const int32_t* plens; const int32_t* slens;
@@ -86,6 +101,7 @@ struct SharedParams {
   TreeLevel lev[MAX_LEVELS];
   int n_lev;
   int n_cu;               // workgroup pairs (pairs_for the device's compute units); the grid is 2 * n_cu workgroups
+  FastDiv div_Hq, div_G, div_r;   // exact quotients by Hq, G and r for the combine kernels' row arithmetic
 };
 
 // the level that entry `e` of the prefix line belongs to (e is wavefront-uniform: scalar selects)
@@ -787,7 +803,7 @@ __global__ void __launch_bounds__(NTHREADS, 2) partial_kernel(const SharedParams
   }
   __syncthreads();
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, REREAD && P.SM == 2);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, P.n_cu, REREAD && P.SM == 2);
   if (blockIdx.x == 0) for (int i = tid; i < n; i += NTHREADS) P.cum[i] = X[i];
   // a small batch works with the first half of the grid (never in the dual partition)
   const int w = REREAD ? (int)blockIdx.x : wg_name(sc, blockIdx.x);
@@ -835,16 +851,16 @@ __global__ void __launch_bounds__(256) combine_kernel(const SharedParams P) {
   const int sub = threadIdx.x & 31, c4 = sub * 4;
   const int coff = part_col_off(sub);                       // where this lane's 4 columns sit in a stored partial row
   if (row >= P.B * P.Hq) return;
-  const int b = row / P.Hq, h = row % P.Hq;
+  const int b = fast_div(row, P.div_Hq), h = row - b * P.Hq;
   if (EXT && P.active && P.active[b] == 0) {               // finished sequence: its prefix rows were computed, not used
     *reinterpret_cast<float4*>(P.out + (size_t)row * D + c4) = make_float4(0.f, 0.f, 0.f, 0.f);
     if (P.lse && c4 == 0) P.lse[row] = -INFINITY;
     return;
   }
-  const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
+  const int p = fast_div(b, P.div_G), gs = b - p * P.G, j = fast_div(h, P.div_r), hi_ = h - j * P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, P.SM == 2);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, P.n_cu, P.SM == 2);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
   const int half = P.RS == 64 ? grow >> 6 : 0, prow = grow - 64 * half;   // row half, row inside it
   const int jp = j * P.NH + (half >> (P.SM - 1)), side = half & (P.SM - 1);  // its unit on the line, which twin computes it
@@ -936,7 +952,7 @@ constexpr int COMBINE16_MIN_UNITS = 128;
 // ---- the same with 16 lanes per row and 16 rows per workgroup, for batches of many units, whose rows
 // have few parts (a prefix unit is cut into about 1 + N_WG / units parts): half the wavefronts, so that
 // 2048 x 16 rows are one resident generation of workgroups instead of two, at the price of a shallower
-// first request (four parts instead of eight), which rows of many parts would pay in round trips.  Lane k of the row first owns part k:
+// first request (four parts instead of sixteen), which rows of many parts would pay in round trips.  Lane k of the row first owns part k:
 // all lse values of the row and the first four parts' values are requested in one round trip; the lse
 // values become weights with two 16-lane reductions; then every lane accumulates its 8 columns, one
 // 16-byte chunk of every stored partial row.  Parts are taken in line order, so the sum has one fixed order.
@@ -947,7 +963,7 @@ __global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P)
   const int coff = 16 * sub;                                // chunk `sub` of a stored partial row holds columns
   const int ca = 32 * (sub >> 2) + 4 * (sub & 3), cb = ca + 16;   // ca .. ca+3 and cb .. cb+3 (see part_col_off)
   if (row >= P.B * P.Hq) return;
-  const int b = row / P.Hq, h = row % P.Hq;
+  const int b = fast_div(row, P.div_Hq), h = row - b * P.Hq;
   float* orow = P.out + (size_t)row * D;
   if (EXT && P.active && P.active[b] == 0) {               // finished sequence: its prefix rows were computed, not used
     *reinterpret_cast<float4*>(orow + ca) = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -955,10 +971,10 @@ __global__ void __launch_bounds__(256, 8) combine16_kernel(const SharedParams P)
     if (P.lse && sub == 0) P.lse[row] = -INFINITY;
     return;
   }
-  const int p = b / P.G, gs = b % P.G, j = h / P.r, hi_ = h % P.r;
+  const int p = fast_div(b, P.div_G), gs = b - p * P.G, j = fast_div(h, P.div_r), hi_ = h - j * P.r;
   const int* X = P.cum;
   const int cumP = X[P.P];
-  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, PREFIX_WEIGHT, SUFFIX_WEIGHT, P.n_cu, P.SM == 2);
+  const Sched sc = make_sched(cumP * P.HkvP, (X[P.P + P.B] - cumP) * P.Hkv, P.n_cu, P.SM == 2);
   const int grow = gs * P.r + hi_;                          // row inside the KV group: sample-major
   const int half = P.RS == 64 ? grow >> 6 : 0, prow = grow - 64 * half;   // row half, row inside it
   const int jp = j * P.NH + (half >> (P.SM - 1)), side = half & (P.SM - 1);  // its unit on the line, which twin computes it
@@ -1479,6 +1495,7 @@ hipError_t launch_shared(const Problem& whole, hipStream_t stream, hipEvent_t mi
   P.sl = reinterpret_cast<float*>(ws + L.sl); P.so = reinterpret_cast<_Float16*>(ws + L.so);
   P.P = (int)n_prefix_entries(ds); P.G = max_group(ds); P.B = (int)n_sequences(ds); P.Hq = ds.Hq; P.Hkv = ds.Hkv;
   P.r = ds.Hq / ds.Hkv; P.R = P.r * P.G; P.Lp_cap = ds.Lp_cap; P.Ls_cap = ds.Ls_cap;
+  P.div_Hq = make_fastdiv(P.Hq); P.div_G = make_fastdiv(P.G); P.div_r = make_fastdiv(P.r);
   P.c = ds.scale * 1.4426950408889634f;
   const bool tree = ds.n_levels > 0;
   P.n_lev = ds.n_levels;

@@ -360,6 +360,20 @@ def test_many_short_sequences_fill_the_length_scan(B, P, plan):
     check(x, 0.1, G, "bf16", "auto", f"P={P}", B)
 
 
+@pytest.mark.parametrize("tiles", [2047, 2048, 2049])
+def test_around_the_tile_count_where_half_the_workgroup_pairs_take_over(B, tiles):
+    """A batch of fewer than 2048 tiles is cut among half the workgroup pairs; the streaming kernel and the
+    combine kernel each decide that from the tile totals on the device.  One KV head, so that one sequence's
+    length moves the total by single tiles: 4 prompts x 16 tiles + 32 sequences x 62 tiles = 2048."""
+    P, G, Hq, Hkv, d = 4, 8, 8, 1, 128
+    pl = np.full(P, 16 * 32, np.int32)
+    sl = np.full(P * G, 62 * 32, np.int32)
+    sl[13] += (tiles - 2048) * 32
+    x = util.random_case(600 + tiles, P, G, Hq, Hkv, d, 16 * 32, 63 * 32, "bf16", plens=pl, slens=sl)
+    assert int((-(-x["prefix_lens"] // 32)).sum() + (-(-x["suffix_lens"] // 32)).sum()) == tiles
+    check(x, 0.09, G, "bf16", "auto", f"{tiles} tiles", B)
+
+
 @pytest.mark.parametrize("paged", [False, True])
 def test_rows_with_many_parts_in_the_16_lane_combine(B, paged):
     """128 prefix units select the 16-lane combine kernel; one prompt and one sequence hold nearly all
