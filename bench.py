@@ -27,8 +27,9 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
 # HBM bytes one launch of the K/V-streaming kernel moved, per workload, from two rocprofv3 --pmc passes
-# (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read for the
-# 1 GiB copy of --copy-probe (profiles/partial_kernel_*_hbm_traffic.md).  Carried over from that profile
+# (FETCH_SIZE, then WRITE_SIZE) over this script, each scaled by what the same counter read for kernels of
+# known size in the same run: the 1 GiB loads-only probe and the 1 GiB copies of --copy-probe, which agree
+# (profiles/partial_kernel_*.md).  Carried over from that profile
 # run, not measured in this one: reported only while the sources the kernel is built from still hash to
 # what the counters were taken on, null otherwise.
 PMC_TRAFFIC = {
