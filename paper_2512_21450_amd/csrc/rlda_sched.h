@@ -18,7 +18,7 @@
 // share of each line (position N*c/n_cu .. N*(c+1)/n_cu), so that every compute
 // unit carries the same mix of work and all finish together.  Inside a pair the
 // two workgroups are evened out by tile weight (a prefix tile costs wP, a suffix
-// tile wS): in a batch whose suffix tiles outweigh its prefix tiles, A takes all
+// tile SUFFIX_WEIGHT): in a batch whose suffix tiles outweigh its prefix tiles, A takes all
 // prefix tiles plus the first few suffix tiles and B the other suffix tiles; in
 // a prefix-heavy batch (short responses behind long multimodal prompts, the
 // first steps of any rollout), A takes prefix tiles only and B the last few
@@ -110,8 +110,8 @@ __host__ __device__ inline Sched make_sched(int NPT, int NST, int n_launch, bool
   return s;
 }
 
-// Lines are limited to MAX_LINE tiles so that the share arithmetic stays in 32 bits (64-bit
-// division is slow on the GPU and the combine kernel does several per row).
+// Lines are limited to MAX_LINE tiles so that the share arithmetic (a line position times the pair count)
+// stays in 32 bits.
 constexpr int MAX_LINE = (1 << 30) / N_CU;
 
 // pair c owns positions [share(N, c), share(N, c + 1)) of a line of N tiles (cu_sh = log2 of the pair count)

@@ -40,3 +40,13 @@ def test_stored_traffic_names_known_workloads():
         assert t["fetch_bytes"] >= 0 and t["write_bytes"] >= 0
     # the hash covers the files the K/V-streaming kernel is built from
     assert len(bench.csrc_sha256()) == 64
+
+
+def test_source_hash_ignores_comments_and_layout_only():
+    sys.path.insert(0, ROOT)
+    import bench
+    a = 'int f(int x) { // doubles\n  return 2 * x; /* twice */ }\nconst char* s = "// kept";\n'
+    b = 'int f(int x) {\n\n  return 2 * x;  }   const char* s = "// kept";'
+    c = 'int f(int x) { return 3 * x; } const char* s = "// kept";'
+    assert bench.strip_comments(a) == bench.strip_comments(b) != bench.strip_comments(c)
+    assert '"// kept"' in bench.strip_comments(a)
