@@ -179,6 +179,17 @@ def test_partition_edge_cases():
         check(P, G, Hkv, Lp_cap, Ls_cap, pl, sl, R=int(rng.choice([7, 56, 64, 65, 128, 129, 256])))
 
 
+def test_partition_of_long_lines():
+    """Millions of tiles on a line: the owner of a line position comes from a float quotient settled by exact
+    steps, which has to hold where the quotient's rounding is coarsest."""
+    rng = np.random.default_rng(5)
+    P, G, Hkv = 512, 8, 4
+    pl = rng.integers(7000, 8193, P)
+    sl = rng.integers(0, 8193, P * G)
+    check(P, G, Hkv, 8192, 8192, pl, sl, R=56)
+    check(64, 16, 2, 100000, 60000, rng.integers(90000, 100001, 64), rng.integers(0, 60001, 64 * 16), R=128, cus=128)
+
+
 def test_pairs_follow_the_compute_unit_count():
     # the largest power of two that is at most the device's compute units and at most 256
     assert [_pairs(c) for c in (256, 304, 255, 128, 100, 64, 33, 32, 2, 1)] == [256, 256, 128, 128, 64, 64, 32, 32, 2, 1]
